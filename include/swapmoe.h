@@ -1,0 +1,181 @@
+/*
+ * libswapmoe -- the Virtual-Expert top-1 MoE layer of SwapMoE on one MI355X.
+ *
+ * One Switch-style MoE layer whose router may only pick from a small resident
+ * set of K "Virtual Experts" out of E (SwapMoE, Section 3.1 "Masked Gating",
+ * Figure 4(b)).  The forward pass is six calls, all enqueued on the caller's
+ * HIP stream, none of which allocates, synchronises or reads back:
+ *
+ *   smoe_route       router product, softmax, original and masked top-1, |x|
+ *   smoe_importance  per-expert importance accumulators (Eq. 1)
+ *   smoe_permute     stable sort of the tokens by resident slot
+ *   smoe_expert_ffn  grouped FFN  ReLU(x W1_k) W2_k  over the sorted rows
+ *   smoe_combine     y = G(x)_i E_i(x) back in token order
+ *   smoe_set_resident  load one expert's weights into a slot (Section 3.2)
+ *
+ * Conventions
+ *   - Plain C ABI.  Every call returns SMOE_OK (0) or a negative smoe_status;
+ *     smoe_last_error() gives a thread-local message for the last failure.
+ *     Arguments are validated before anything is launched.
+ *   - Unless marked "host", every pointer is a DEVICE pointer owned by the
+ *     caller, who keeps it alive until the stream work that uses it is done.
+ *     The library owns only the opaque handle (host memory).
+ *   - All matrices are row-major and dense.  Activations and expert weights
+ *     have the dtype given in smoe_config (fp32, or bf16 stored as uint16 bit
+ *     patterns); router weights, gates, norms and scores are fp32; indices and
+ *     counts are int32.
+ *   - T is a host integer, 0 <= T <= max_tokens; T = 0 is a legal no-op.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Calls on one handle must be issued from one thread at a time, and stream
+ *     work of consecutive calls on one handle must be ordered (same stream, or
+ *     event dependencies), because they share the bound workspace.
+ *   - NaN / Inf inputs give undefined results.
+ */
+#ifndef SWAPMOE_H
+#define SWAPMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SMOE_OK = 0,
+    SMOE_EINVAL = -1,   /* bad argument: null pointer, size out of range, unknown enum   */
+    SMOE_ESTATE = -2,   /* call not legal in the handle's state (unbound, slots unset, ...) */
+    SMOE_EHIP = -3,     /* the HIP runtime reported an error; text in smoe_last_error()  */
+    SMOE_ENOMEM = -4    /* host allocation for the handle failed                         */
+} smoe_status;
+
+enum { SMOE_F32 = 0, SMOE_BF16 = 1 };
+enum { SMOE_GATE_FULL = 0, SMOE_GATE_RENORM = 1 };
+
+typedef struct smoe_layer smoe_layer_t;
+
+/* Layer shape.  E experts in the full bank, K resident slots (1 <= K <= E),
+ * d_model -> d_ff -> ReLU -> d_model experts without biases.  dtype is the
+ * storage type of activations AND expert weights (SMOE_F32 or SMOE_BF16).
+ * gate_mode: SMOE_GATE_FULL  gate = softmax over all E, read at the served expert;
+ *            SMOE_GATE_RENORM the same divided by the resident experts' total.
+ * Limits: E <= 256; K <= E; for SMOE_BF16, d_model and d_ff must be
+ * multiples of 32 (the MFMA fragment width); max_tokens >= 1. */
+typedef struct {
+    int32_t E, K, d_model, d_ff, max_tokens;
+    int32_t dtype;
+    int32_t gate_mode;
+} smoe_config;
+
+/* Creates a handle (host memory only; no HIP call is made).  *out is set to
+ * NULL on failure.  Initially no slot holds an expert. */
+int smoe_create(const smoe_config* cfg /*host*/, smoe_layer_t** out /*host*/);
+int smoe_destroy(smoe_layer_t* layer);
+
+/* Thread-local text of the last error returned on this thread ("" if none). */
+const char* smoe_last_error(void);
+
+/* Bytes of device workspace smoe_bind() needs (maps, sort histograms, the
+ * FFN's hidden activations for max_tokens rows).  0 if layer is NULL. */
+size_t smoe_workspace_bytes(const smoe_layer_t* layer);
+
+/* Bytes of ONE of the two slot weight arrays (slot_w1 or slot_w2) for all K
+ * slots.  The arrays are opaque to the caller: for SMOE_BF16 the library keeps
+ * each slot in a tiled order that feeds the matrix cores with contiguous loads
+ * (see smoe_set_resident), so they can only be filled through
+ * smoe_set_resident.  Equals K * d_model * d_ff * sizeof(dtype). */
+size_t smoe_slot_weight_bytes(const smoe_layer_t* layer);
+
+/* Binds the caller-owned device buffers the layer works on.
+ *   router_w    [E, d_model] fp32, the router G's weight (no bias)
+ *   slot_w1/2   smoe_slot_weight_bytes() each, 256-byte aligned, contents
+ *               written only by smoe_set_resident
+ *   expert_norm [E] fp32, |E_i| of Eq. 1 for every expert of the bank
+ *               (e.g. from smoe_expert_norm); read by smoe_importance
+ *   workspace   smoe_workspace_bytes() bytes, 256-byte aligned
+ * Rebinding is allowed and marks every slot empty again. */
+int smoe_bind(smoe_layer_t* layer, const float* router_w, void* slot_w1, void* slot_w2,
+              const float* expert_norm, void* workspace);
+
+/* |E_i| of Eq. 1 for n experts stored in bank layout: w1 [n, d_model, d_ff],
+ * w2 [n, d_ff, d_model] in the layer's dtype -> out [n] fp32, the Frobenius
+ * norm of all of the expert's parameters, sqrt(|W1_i|^2 + |W2_i|^2).  The same
+ * magnitude ranks experts in the paper's "Pruning" baseline (Section 4.1). */
+int smoe_expert_norm(smoe_layer_t* layer, const void* w1, const void* w2, int n, float* out,
+                     void* stream);
+
+/* Virtual-Expert update (Section 3.2): puts `expert` into `slot`.  Reads the
+ * expert's weights in bank layout, w1_src [d_model, d_ff] and w2_src
+ * [d_ff, d_model] (device memory, or pinned host memory mapped into the
+ * device), and writes them into the slot arrays in the library's tiled order;
+ * updates the slot<->expert maps on the host and, in stream order, on the
+ * device.  The previous occupant of the slot stops being resident.
+ * Errors: slot outside [0,K) or expert outside [0,E) -> SMOE_EINVAL; expert
+ * already resident in a DIFFERENT slot -> SMOE_ESTATE (same slot = refresh). */
+int smoe_set_resident(smoe_layer_t* layer, int slot, int expert, const void* w1_src,
+                      const void* w2_src, void* stream);
+
+/* Host copies of the maps: slot_to_expert [K] (-1 = empty), expert_to_slot [E]
+ * (-1 = not resident).  Either pointer may be NULL. */
+int smoe_get_maps(const smoe_layer_t* layer, int32_t* slot_to_expert /*host*/,
+                  int32_t* expert_to_slot /*host*/);
+
+/* Update policy (Section 3.2: important experts in, unimportant out), host
+ * only: given score [E] (host), the new resident set is the K highest-scoring
+ * experts (ties: lower expert id); experts that stay keep their slot; freed
+ * slots in ascending order receive incoming experts in descending score
+ * order.  Nothing is changed in the handle: the (slot, expert) pairs to load
+ * are written to changed_slots / changed_experts (host, capacity K) and their
+ * number is returned (>= 0), or a negative smoe_status.  The caller then calls
+ * smoe_set_resident for each pair, in the order given. */
+int smoe_select_resident(const smoe_layer_t* layer, const float* score /*host*/,
+                         int32_t* changed_slots /*host*/, int32_t* changed_experts /*host*/);
+
+/* Router (Background: G(x), "the i-th expert with max G(x)_i is activated")
+ * and Masked Gating (Section 3.1).  For each token t of x [T, d_model]:
+ *   logit = x_t . router_w^T (fp32), p = softmax(logit) over all E;
+ *   orig_expert[t] = argmax_e logit (lowest id on a tie), orig_gate[t] = p[orig];
+ *   s = argmax over RESIDENT experts of the same logits;
+ *   slot[t] = slot holding s, gate[t] per gate_mode; xnorm[t] = |x_t|_2.
+ * SMOE_ESTATE until every slot has been filled by smoe_set_resident. */
+int smoe_route(smoe_layer_t* layer, const void* x, int T, int32_t* orig_expert, float* orig_gate,
+               int32_t* slot, float* gate, float* xnorm, void* stream);
+
+/* Importance accumulation (Eq. 1), over X_i = tokens whose ORIGINAL choice is i:
+ *   count[i] (+)= |X_i|                      the "simple scheduling" score (Section 4.5)
+ *   gsum[i]  (+)= sum_{t in X_i} orig_gate[t]
+ *   score[i] (+)= expert_norm[i] * sum_{t in X_i} xnorm[t] * orig_gate[t]   (Eq. 1)
+ * for all i in [0,E).  accumulate = 0 overwrites, 1 adds to the arrays'
+ * current contents.  Deterministic: no atomics, fixed summation order. */
+int smoe_importance(smoe_layer_t* layer, const int32_t* orig_expert, const float* orig_gate,
+                    const float* xnorm, int T, int32_t* count, float* gsum, float* score,
+                    int accumulate, void* stream);
+
+/* Stable counting sort of the tokens by slot (each token goes to exactly one
+ * resident expert, no capacity limit, no dropping): segments in slot order,
+ * ascending token index inside a segment.
+ *   offsets[k] = #tokens with slot < k, k in [0,K]; perm[pos] = token;
+ *   inv_perm[token] = pos; x_perm[pos, :] = x[perm[pos], :].
+ * slot values must lie in [0,K) (as smoe_route writes them). */
+int smoe_permute(smoe_layer_t* layer, const void* x, const int32_t* slot, int T, void* x_perm,
+                 int32_t* perm, int32_t* inv_perm, int32_t* offsets, void* stream);
+
+/* Grouped expert FFN, E_i(x) of the Background section: rows
+ * [offsets[k], offsets[k+1]) of x_perm [T, d_model] belong to slot k and get
+ *   y_perm[r, :] = ReLU(x_perm[r, :] . W1_k) . W2_k          (no biases)
+ * bf16: matrix-core products with fp32 accumulation, the hidden activations
+ * are rounded to bf16 between the two products.  offsets is the device array
+ * smoe_permute wrote (non-decreasing, offsets[0] = 0, offsets[K] = T). */
+int smoe_expert_ffn(smoe_layer_t* layer, const void* x_perm, const int32_t* offsets, int T,
+                    void* y_perm, void* stream);
+
+/* Gate-weighted combine, y = G(x)_i E_i(x) in token order:
+ *   out[t, :] = gate[t] * y_perm[inv_perm[t], :]  (+ residual[t, :] if not NULL)
+ * computed in fp32 and rounded once to the layer's dtype. */
+int smoe_combine(smoe_layer_t* layer, const void* y_perm, const int32_t* inv_perm, const float* gate,
+                 const void* residual, int T, void* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SWAPMOE_H */

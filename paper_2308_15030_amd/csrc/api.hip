@@ -1,0 +1,272 @@
+// C ABI of libswapmoe: handle life cycle, argument validation, the host side
+// of the slot<->expert maps (the Virtual-Expert bookkeeping of SwapMoE,
+// abstract and Section 3.2) and the update policy.  No kernel lives here.
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <algorithm>
+#include <new>
+#include <numeric>
+
+#include "smoe_internal.h"
+
+namespace {
+thread_local char g_err[512] = "";
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+hipStream_t as_stream(void* s) { return (hipStream_t)s; }
+
+bool misaligned(const void* p, size_t a) { return ((uintptr_t)p % a) != 0; }
+}  // namespace
+
+int smoe_fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int smoe_check_hip(hipError_t e, const char* what) {
+    if (e == hipSuccess) return SMOE_OK;
+    return smoe_fail(SMOE_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+smoe_ws_layout smoe_ws_plan(const smoe_config& c) {
+    smoe_ws_layout w{};
+    size_t off = 0;
+    w.e2s = off;     off = align_up(off + (size_t)c.E * 4, 256);
+    w.s2e = off;     off = align_up(off + (size_t)c.K * 4, 256);
+    w.hist = off;    off = align_up(off + (size_t)smoe_sort_blocks(c.max_tokens) * c.K * 4, 256);
+    w.hidden = off;  off = align_up(off + (size_t)c.max_tokens * c.d_ff * smoe_elem_size(c.dtype), 256);
+    w.partial = off; off = align_up(off, 256);
+    w.total = off;
+    return w;
+}
+
+extern "C" {
+
+const char* smoe_last_error(void) { return g_err; }
+
+int smoe_create(const smoe_config* cfg, smoe_layer_t** out) {
+    if (out) *out = nullptr;
+    if (!cfg || !out) return smoe_fail(SMOE_EINVAL, "smoe_create: null argument");
+    const smoe_config& c = *cfg;
+    if (c.E < 1 || c.E > 256) return smoe_fail(SMOE_EINVAL, "smoe_create: E=%d outside [1,256]", c.E);
+    if (c.K < 1 || c.K > c.E)
+        return smoe_fail(SMOE_EINVAL, "smoe_create: K=%d outside [1,E]", c.K);
+    if (c.d_model < 1 || c.d_ff < 1 || c.d_model > (1 << 16) || c.d_ff > (1 << 18))
+        return smoe_fail(SMOE_EINVAL, "smoe_create: d_model=%d d_ff=%d out of range", c.d_model, c.d_ff);
+    if (c.max_tokens < 1 || c.max_tokens > (1 << 24))
+        return smoe_fail(SMOE_EINVAL, "smoe_create: max_tokens=%d outside [1,2^24]", c.max_tokens);
+    if (c.dtype != SMOE_F32 && c.dtype != SMOE_BF16)
+        return smoe_fail(SMOE_EINVAL, "smoe_create: unknown dtype %d", c.dtype);
+    if (c.gate_mode != SMOE_GATE_FULL && c.gate_mode != SMOE_GATE_RENORM)
+        return smoe_fail(SMOE_EINVAL, "smoe_create: unknown gate_mode %d", c.gate_mode);
+    if (c.dtype == SMOE_BF16 && (c.d_model % 32 || c.d_ff % 32))
+        return smoe_fail(SMOE_EINVAL, "smoe_create: bf16 needs d_model and d_ff to be multiples of 32");
+    if (c.dtype == SMOE_F32 && (c.d_model % 4 || c.d_ff % 4))
+        return smoe_fail(SMOE_EINVAL, "smoe_create: fp32 needs d_model and d_ff to be multiples of 4");
+    smoe_layer* L = new (std::nothrow) smoe_layer();
+    if (!L) return smoe_fail(SMOE_ENOMEM, "smoe_create: out of host memory");
+    L->cfg = c;
+    L->slot_to_expert.assign(c.K, -1);
+    L->expert_to_slot.assign(c.E, -1);
+    *out = L;
+    return SMOE_OK;
+}
+
+int smoe_destroy(smoe_layer_t* layer) {
+    if (!layer) return smoe_fail(SMOE_EINVAL, "smoe_destroy: null handle");
+    delete layer;
+    return SMOE_OK;
+}
+
+size_t smoe_workspace_bytes(const smoe_layer_t* layer) {
+    return layer ? smoe_ws_plan(layer->cfg).total : 0;
+}
+
+size_t smoe_slot_weight_bytes(const smoe_layer_t* layer) {
+    if (!layer) return 0;
+    const smoe_config& c = layer->cfg;
+    return (size_t)c.K * c.d_model * c.d_ff * smoe_elem_size(c.dtype);
+}
+
+int smoe_bind(smoe_layer_t* L, const float* router_w, void* slot_w1, void* slot_w2,
+              const float* expert_norm, void* workspace) {
+    if (!L) return smoe_fail(SMOE_EINVAL, "smoe_bind: null handle");
+    if (!router_w || !slot_w1 || !slot_w2 || !expert_norm || !workspace)
+        return smoe_fail(SMOE_EINVAL, "smoe_bind: null buffer");
+    if (misaligned(slot_w1, 256) || misaligned(slot_w2, 256) || misaligned(workspace, 256))
+        return smoe_fail(SMOE_EINVAL, "smoe_bind: slot arrays and workspace must be 256-byte aligned");
+    if (misaligned(router_w, 16) || misaligned(expert_norm, 4))
+        return smoe_fail(SMOE_EINVAL, "smoe_bind: router_w must be 16-byte aligned");
+    smoe_ws_layout w = smoe_ws_plan(L->cfg);
+    L->router_w = router_w;
+    L->slot_w1 = slot_w1;
+    L->slot_w2 = slot_w2;
+    L->expert_norm = expert_norm;
+    L->workspace = (char*)workspace;
+    L->d_expert_to_slot = (int32_t*)(L->workspace + w.e2s);
+    L->d_slot_to_expert = (int32_t*)(L->workspace + w.s2e);
+    L->d_sort_hist = (int32_t*)(L->workspace + w.hist);
+    L->d_hidden = L->workspace + w.hidden;
+    L->d_partial = (float*)(L->workspace + w.partial);
+    std::fill(L->slot_to_expert.begin(), L->slot_to_expert.end(), -1);
+    std::fill(L->expert_to_slot.begin(), L->expert_to_slot.end(), -1);
+    L->slots_set = 0;
+    L->bound = true;
+    return SMOE_OK;
+}
+
+int smoe_get_maps(const smoe_layer_t* L, int32_t* slot_to_expert, int32_t* expert_to_slot) {
+    if (!L) return smoe_fail(SMOE_EINVAL, "smoe_get_maps: null handle");
+    if (slot_to_expert) std::memcpy(slot_to_expert, L->slot_to_expert.data(), (size_t)L->cfg.K * 4);
+    if (expert_to_slot) std::memcpy(expert_to_slot, L->expert_to_slot.data(), (size_t)L->cfg.E * 4);
+    return SMOE_OK;
+}
+
+int smoe_expert_norm(smoe_layer_t* L, const void* w1, const void* w2, int n, float* out, void* stream) {
+    if (!L) return smoe_fail(SMOE_EINVAL, "smoe_expert_norm: null handle");
+    if (n < 0) return smoe_fail(SMOE_EINVAL, "smoe_expert_norm: n=%d < 0", n);
+    if (n == 0) return SMOE_OK;
+    if (!w1 || !w2 || !out) return smoe_fail(SMOE_EINVAL, "smoe_expert_norm: null buffer");
+    if (misaligned(w1, 16) || misaligned(w2, 16))
+        return smoe_fail(SMOE_EINVAL, "smoe_expert_norm: weights must be 16-byte aligned");
+    return smoe_launch_expert_norm(L, w1, w2, n, out, as_stream(stream));
+}
+
+int smoe_set_resident(smoe_layer_t* L, int slot, int expert, const void* w1_src, const void* w2_src,
+                      void* stream) {
+    if (!L) return smoe_fail(SMOE_EINVAL, "smoe_set_resident: null handle");
+    if (!L->bound) return smoe_fail(SMOE_ESTATE, "smoe_set_resident: call smoe_bind first");
+    const smoe_config& c = L->cfg;
+    if (slot < 0 || slot >= c.K) return smoe_fail(SMOE_EINVAL, "smoe_set_resident: slot %d outside [0,%d)", slot, c.K);
+    if (expert < 0 || expert >= c.E)
+        return smoe_fail(SMOE_EINVAL, "smoe_set_resident: expert %d outside [0,%d)", expert, c.E);
+    if (!w1_src || !w2_src) return smoe_fail(SMOE_EINVAL, "smoe_set_resident: null weight source");
+    if (misaligned(w1_src, 16) || misaligned(w2_src, 16))
+        return smoe_fail(SMOE_EINVAL, "smoe_set_resident: weight sources must be 16-byte aligned");
+    int cur = L->expert_to_slot[expert];
+    if (cur >= 0 && cur != slot)
+        return smoe_fail(SMOE_ESTATE, "smoe_set_resident: expert %d is already resident in slot %d", expert, cur);
+    hipStream_t s = as_stream(stream);
+    if (L->slots_set == 0) {
+        // first load after a bind: the device maps are uninitialised memory
+        int rc = smoe_launch_clear_maps(L, s);
+        if (rc) return rc;
+    }
+    int old = L->slot_to_expert[slot];
+    int rc = smoe_launch_load_slot(L, slot, expert, old, w1_src, w2_src, s);
+    if (rc) return rc;
+    if (old >= 0) L->expert_to_slot[old] = -1; else L->slots_set += 1;
+    L->slot_to_expert[slot] = expert;
+    L->expert_to_slot[expert] = slot;
+    return SMOE_OK;
+}
+
+int smoe_select_resident(const smoe_layer_t* L, const float* score, int32_t* changed_slots,
+                         int32_t* changed_experts) {
+    if (!L) return smoe_fail(SMOE_EINVAL, "smoe_select_resident: null handle");
+    if (!score || !changed_slots || !changed_experts)
+        return smoe_fail(SMOE_EINVAL, "smoe_select_resident: null argument");
+    const int E = L->cfg.E, K = L->cfg.K;
+    // rank experts: higher score first, lower id first among equals
+    std::vector<int> rank(E);
+    std::iota(rank.begin(), rank.end(), 0);
+    std::sort(rank.begin(), rank.end(), [&](int a, int b) {
+        return score[a] != score[b] ? score[a] > score[b] : a < b;
+    });
+    std::vector<char> wanted(E, 0);
+    for (int i = 0; i < K; ++i) wanted[rank[i]] = 1;
+    // walk the free slots upwards and the newcomers downwards in score
+    int n = 0, ri = 0;
+    for (int s = 0; s < K; ++s) {
+        int cur = L->slot_to_expert[s];
+        if (cur >= 0 && wanted[cur]) continue;
+        while (ri < K && L->expert_to_slot[rank[ri]] >= 0) ++ri;
+        if (ri >= K) return smoe_fail(SMOE_ESTATE, "smoe_select_resident: inconsistent maps");
+        changed_slots[n] = s;
+        changed_experts[n] = rank[ri++];
+        ++n;
+    }
+    return n;
+}
+
+// ---- the hot calls: validate, then hand over to the launchers -------------
+
+static int check_hot(const smoe_layer* L, int T, const char* who, bool need_full) {
+    if (!L) return smoe_fail(SMOE_EINVAL, "%s: null handle", who);
+    if (!L->bound) return smoe_fail(SMOE_ESTATE, "%s: call smoe_bind first", who);
+    if (T < 0 || T > L->cfg.max_tokens)
+        return smoe_fail(SMOE_EINVAL, "%s: T=%d outside [0,%d]", who, T, L->cfg.max_tokens);
+    if (need_full && L->slots_set != L->cfg.K)
+        return smoe_fail(SMOE_ESTATE, "%s: only %d of %d slots hold an expert", who, L->slots_set, L->cfg.K);
+    return SMOE_OK;
+}
+
+int smoe_route(smoe_layer_t* L, const void* x, int T, int32_t* orig_expert, float* orig_gate,
+               int32_t* slot, float* gate, float* xnorm, void* stream) {
+    int rc = check_hot(L, T, "smoe_route", true);
+    if (rc) return rc;
+    if (T == 0) return SMOE_OK;
+    if (!x || !orig_expert || !orig_gate || !slot || !gate || !xnorm)
+        return smoe_fail(SMOE_EINVAL, "smoe_route: null buffer");
+    if (misaligned(x, 16)) return smoe_fail(SMOE_EINVAL, "smoe_route: x must be 16-byte aligned");
+    return smoe_launch_route(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, as_stream(stream));
+}
+
+int smoe_importance(smoe_layer_t* L, const int32_t* orig_expert, const float* orig_gate,
+                    const float* xnorm, int T, int32_t* count, float* gsum, float* score,
+                    int accumulate, void* stream) {
+    int rc = check_hot(L, T, "smoe_importance", false);
+    if (rc) return rc;
+    if (accumulate != 0 && accumulate != 1)
+        return smoe_fail(SMOE_EINVAL, "smoe_importance: accumulate must be 0 or 1");
+    if (!count || !gsum || !score) return smoe_fail(SMOE_EINVAL, "smoe_importance: null output");
+    if (T > 0 && (!orig_expert || !orig_gate || !xnorm))
+        return smoe_fail(SMOE_EINVAL, "smoe_importance: null input");
+    if (T == 0 && accumulate == 1) return SMOE_OK;
+    return smoe_launch_importance(L, orig_expert, orig_gate, xnorm, T, count, gsum, score, accumulate,
+                                  as_stream(stream));
+}
+
+int smoe_permute(smoe_layer_t* L, const void* x, const int32_t* slot, int T, void* x_perm,
+                 int32_t* perm, int32_t* inv_perm, int32_t* offsets, void* stream) {
+    int rc = check_hot(L, T, "smoe_permute", false);
+    if (rc) return rc;
+    if (!offsets) return smoe_fail(SMOE_EINVAL, "smoe_permute: null offsets");
+    if (T > 0 && (!x || !slot || !x_perm || !perm || !inv_perm))
+        return smoe_fail(SMOE_EINVAL, "smoe_permute: null buffer");
+    if (T > 0 && (misaligned(x, 16) || misaligned(x_perm, 16)))
+        return smoe_fail(SMOE_EINVAL, "smoe_permute: x and x_perm must be 16-byte aligned");
+    return smoe_launch_permute(L, x, slot, T, x_perm, perm, inv_perm, offsets, as_stream(stream));
+}
+
+int smoe_expert_ffn(smoe_layer_t* L, const void* x_perm, const int32_t* offsets, int T, void* y_perm,
+                    void* stream) {
+    int rc = check_hot(L, T, "smoe_expert_ffn", true);
+    if (rc) return rc;
+    if (T == 0) return SMOE_OK;
+    if (!x_perm || !offsets || !y_perm) return smoe_fail(SMOE_EINVAL, "smoe_expert_ffn: null buffer");
+    if (misaligned(x_perm, 16) || misaligned(y_perm, 16))
+        return smoe_fail(SMOE_EINVAL, "smoe_expert_ffn: x_perm and y_perm must be 16-byte aligned");
+    if (L->cfg.dtype == SMOE_F32)
+        return smoe_launch_ffn_f32(L, (const float*)x_perm, offsets, T, (float*)y_perm, as_stream(stream));
+    return smoe_launch_ffn_bf16(L, (const uint16_t*)x_perm, offsets, T, (uint16_t*)y_perm, as_stream(stream));
+}
+
+int smoe_combine(smoe_layer_t* L, const void* y_perm, const int32_t* inv_perm, const float* gate,
+                 const void* residual, int T, void* out, void* stream) {
+    int rc = check_hot(L, T, "smoe_combine", false);
+    if (rc) return rc;
+    if (T == 0) return SMOE_OK;
+    if (!y_perm || !inv_perm || !gate || !out) return smoe_fail(SMOE_EINVAL, "smoe_combine: null buffer");
+    if (misaligned(y_perm, 16) || misaligned(out, 16) || (residual && misaligned(residual, 16)))
+        return smoe_fail(SMOE_EINVAL, "smoe_combine: y_perm, residual and out must be 16-byte aligned");
+    return smoe_launch_combine(L, y_perm, inv_perm, gate, residual, T, out, as_stream(stream));
+}
+
+}  // extern "C"

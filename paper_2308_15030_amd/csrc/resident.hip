@@ -1,0 +1,159 @@
+// smoe_set_resident's device side: the Virtual-Expert update of SwapMoE
+// (Section 3.2) -- one expert's weights enter a slot and the slot<->expert maps
+// change in stream order -- plus the per-expert magnitude |E_i| of Eq. 1.
+//
+// bf16 slots are kept in MFMA fragment order so the FFN streams them with
+// contiguous 16-byte loads per lane and no LDS transpose.  For a weight matrix
+// B [R, N] (R = reduction length, N = output features; W1: R = d_model,
+// N = d_ff; W2: R = d_ff, N = d_model), element (r, n) lives at
+//     ((n/32 * R/16 + r/16) * 64 + lane) * 8 + r%8,   lane = n%32 + 32*((r%16)/8)
+// i.e. one 1-KiB block per (32 features x 16 reduction steps): exactly one
+// operand of the 32x32x16 bf16 MFMA, lane-major, and all blocks of one feature
+// group contiguous along the reduction.  fp32 slots keep the bank layout.
+
+#include "smoe_internal.h"
+
+namespace {
+
+__global__ void clear_maps_kernel(int32_t* e2s, int E, int32_t* s2e, int K) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < E) e2s[i] = -1;
+    if (i < K) s2e[i] = -1;
+}
+
+__global__ void set_map_kernel(int32_t* e2s, int32_t* s2e, int slot, int expert, int old_expert) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        if (old_expert >= 0) e2s[old_expert] = -1;
+        e2s[expert] = slot;
+        s2e[slot] = expert;
+    }
+}
+
+// One thread builds one 16-byte packed unit: 8 consecutive reduction rows of
+// one feature column.  Within a wave the 32 feature columns are adjacent, so
+// each of the 8 row reads is a 64-byte run and the write is a full 1-KiB block.
+__global__ __launch_bounds__(256) void pack_bf16_kernel(const uint16_t* __restrict__ src, int R, int N,
+                                                        uint4* __restrict__ dst) {
+    size_t unit = (size_t)blockIdx.x * 256 + threadIdx.x;        // = (nb * R/16 + rb) * 64 + lane
+    size_t total = (size_t)(N / 32) * (R / 16) * 64;
+    if (unit >= total) return;
+    int lane = (int)(unit & 63);
+    size_t blk = unit >> 6;
+    int rb = (int)(blk % (R / 16)), nb = (int)(blk / (R / 16));
+    int n = nb * 32 + (lane & 31);
+    int r0 = rb * 16 + (lane >> 5) * 8;
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        uint32_t lo = src[(size_t)(r0 + 2 * i) * N + n];
+        uint32_t hi = src[(size_t)(r0 + 2 * i + 1) * N + n];
+        w[i] = lo | (hi << 16);
+    }
+    dst[unit] = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+__global__ __launch_bounds__(256) void copy16_kernel(const uint4* __restrict__ src, size_t n16,
+                                                     uint4* __restrict__ dst) {
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n16) dst[i] = src[i];
+}
+
+// |E_i|^2 partial sums: grid (chunks, experts); a fixed tree per block and a
+// fixed-order final pass keep the result reproducible.
+constexpr int NORM_CHUNKS = 64;
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void sumsq_kernel(const uint4* __restrict__ w1, const uint4* __restrict__ w2,
+                                                    size_t n16_per_expert, float* __restrict__ partial) {
+    __shared__ float red[256];
+    const int e = blockIdx.y, chunk = blockIdx.x, tid = threadIdx.x;
+    float acc = 0.f;
+    for (int m = 0; m < 2; ++m) {
+        const uint4* w = (m == 0 ? w1 : w2) + (size_t)e * n16_per_expert;
+        for (size_t i = (size_t)chunk * 256 + tid; i < n16_per_expert; i += (size_t)NORM_CHUNKS * 256) {
+            uint4 v = w[i];
+            uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (BF16) {
+                    float lo = __uint_as_float(u[j] << 16), hi = __uint_as_float(u[j] & 0xFFFF0000u);
+                    acc = fmaf(lo, lo, acc);
+                    acc = fmaf(hi, hi, acc);
+                } else {
+                    float f = __uint_as_float(u[j]);
+                    acc = fmaf(f, f, acc);
+                }
+            }
+        }
+    }
+    red[tid] = acc;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if (tid < s) red[tid] += red[tid + s];
+        __syncthreads();
+    }
+    if (tid == 0) partial[(size_t)e * NORM_CHUNKS + chunk] = red[0];
+}
+
+__global__ void norm_finish_kernel(const float* __restrict__ partial, int n, float* __restrict__ out) {
+    int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n) return;
+    float s = 0.f;
+    for (int c = 0; c < NORM_CHUNKS; ++c) s += partial[(size_t)e * NORM_CHUNKS + c];
+    out[e] = sqrtf(s);
+}
+
+}  // namespace
+
+int smoe_launch_clear_maps(const smoe_layer* L, hipStream_t s) {
+    int n = L->cfg.E > L->cfg.K ? L->cfg.E : L->cfg.K;
+    hipLaunchKernelGGL(clear_maps_kernel, dim3((n + 255) / 256), dim3(256), 0, s, L->d_expert_to_slot,
+                       L->cfg.E, L->d_slot_to_expert, L->cfg.K);
+    return smoe_check_hip(hipGetLastError(), "smoe_set_resident: map reset");
+}
+
+int smoe_launch_load_slot(const smoe_layer* L, int slot, int expert, int old_expert,
+                          const void* w1_src, const void* w2_src, hipStream_t s) {
+    const smoe_config& c = L->cfg;
+    const size_t per = (size_t)c.d_model * c.d_ff;               // elements per matrix
+    if (c.dtype == SMOE_BF16) {
+        size_t units = per / 8;
+        dim3 grid((unsigned)((units + 255) / 256));
+        uint4* d1 = (uint4*)((uint16_t*)L->slot_w1 + (size_t)slot * per);
+        uint4* d2 = (uint4*)((uint16_t*)L->slot_w2 + (size_t)slot * per);
+        hipLaunchKernelGGL(pack_bf16_kernel, grid, dim3(256), 0, s, (const uint16_t*)w1_src, c.d_model,
+                           c.d_ff, d1);
+        hipLaunchKernelGGL(pack_bf16_kernel, grid, dim3(256), 0, s, (const uint16_t*)w2_src, c.d_ff,
+                           c.d_model, d2);
+    } else {
+        size_t n16 = per * 4 / 16;
+        dim3 grid((unsigned)((n16 + 255) / 256));
+        hipLaunchKernelGGL(copy16_kernel, grid, dim3(256), 0, s, (const uint4*)w1_src, n16,
+                           (uint4*)((float*)L->slot_w1 + (size_t)slot * per));
+        hipLaunchKernelGGL(copy16_kernel, grid, dim3(256), 0, s, (const uint4*)w2_src, n16,
+                           (uint4*)((float*)L->slot_w2 + (size_t)slot * per));
+    }
+    hipLaunchKernelGGL(set_map_kernel, dim3(1), dim3(64), 0, s, L->d_expert_to_slot, L->d_slot_to_expert,
+                       slot, expert, old_expert);
+    return smoe_check_hip(hipGetLastError(), "smoe_set_resident launch");
+}
+
+int smoe_launch_expert_norm(const smoe_layer* L, const void* w1, const void* w2, int n, float* out,
+                            hipStream_t s) {
+    // The partial sums live in the FFN's hidden-activation area of the workspace
+    // (n * 64 floats); the layer must be bound and n * 256 bytes must fit.
+    if (!L->bound) return smoe_fail(SMOE_ESTATE, "smoe_expert_norm: call smoe_bind first");
+    const smoe_config& c = L->cfg;
+    size_t avail = (size_t)c.max_tokens * c.d_ff * smoe_elem_size(c.dtype);
+    if ((size_t)n * NORM_CHUNKS * 4 > avail)
+        return smoe_fail(SMOE_EINVAL, "smoe_expert_norm: n=%d too large for the bound workspace", n);
+    float* partial = (float*)L->d_hidden;
+    size_t n16 = (size_t)c.d_model * c.d_ff * smoe_elem_size(c.dtype) / 16;
+    dim3 grid(NORM_CHUNKS, n);
+    if (c.dtype == SMOE_BF16)
+        hipLaunchKernelGGL(sumsq_kernel<true>, grid, dim3(256), 0, s, (const uint4*)w1, (const uint4*)w2, n16, partial);
+    else
+        hipLaunchKernelGGL(sumsq_kernel<false>, grid, dim3(256), 0, s, (const uint4*)w1, (const uint4*)w2, n16, partial);
+    hipLaunchKernelGGL(norm_finish_kernel, dim3((n + 63) / 64), dim3(64), 0, s, partial, n, out);
+    return smoe_check_hip(hipGetLastError(), "smoe_expert_norm launch");
+}

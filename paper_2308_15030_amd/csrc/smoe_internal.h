@@ -1,0 +1,79 @@
+// Internal declarations shared by the translation units of libswapmoe.
+// Nothing here is part of the C ABI (see include/swapmoe.h for that).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <vector>
+
+#include "swapmoe.h"
+
+// Tokens handled by one workgroup of the sort kernels (histogram + ranking).
+constexpr int SMOE_SORT_BLOCK = 1024;
+// Upper bound on d_ff tiles / token tiles is derived from the config at bind time.
+
+struct smoe_layer {
+    smoe_config cfg;
+    bool bound = false;
+    int slots_set = 0;                       // number of slots that hold an expert
+    std::vector<int32_t> slot_to_expert;     // host copies of the maps
+    std::vector<int32_t> expert_to_slot;
+
+    // caller-owned device buffers
+    const float* router_w = nullptr;
+    void* slot_w1 = nullptr;
+    void* slot_w2 = nullptr;
+    const float* expert_norm = nullptr;
+    char* workspace = nullptr;
+
+    // carved out of the workspace (device)
+    int32_t* d_expert_to_slot = nullptr;     // [E]
+    int32_t* d_slot_to_expert = nullptr;     // [K]
+    int32_t* d_sort_hist = nullptr;          // [sort blocks, K]
+    void* d_hidden = nullptr;                // [max_tokens, d_ff] activations of the FFN
+    float* d_partial = nullptr;              // small-T FFN: split partial sums
+};
+
+struct smoe_ws_layout {
+    size_t e2s, s2e, hist, hidden, partial, total;
+};
+smoe_ws_layout smoe_ws_plan(const smoe_config& c);
+
+int smoe_fail(int code, const char* fmt, ...);
+int smoe_check_hip(hipError_t e, const char* what);
+
+inline size_t smoe_elem_size(int dtype) { return dtype == SMOE_BF16 ? 2 : 4; }
+inline int smoe_sort_blocks(int T) { return (T + SMOE_SORT_BLOCK - 1) / SMOE_SORT_BLOCK; }
+
+// Kernel launchers, one per translation unit.  All validate nothing: the ABI
+// layer has done that.  Each returns a smoe_status.
+int smoe_launch_route(const smoe_layer* L, const void* x, int T, int32_t* orig_expert,
+                      float* orig_gate, int32_t* slot, float* gate, float* xnorm, hipStream_t s);
+int smoe_launch_importance(const smoe_layer* L, const int32_t* orig_expert, const float* orig_gate,
+                           const float* xnorm, int T, int32_t* count, float* gsum, float* score,
+                           int accumulate, hipStream_t s);
+int smoe_launch_permute(const smoe_layer* L, const void* x, const int32_t* slot, int T, void* x_perm,
+                        int32_t* perm, int32_t* inv_perm, int32_t* offsets, hipStream_t s);
+int smoe_launch_ffn_f32(const smoe_layer* L, const float* x_perm, const int32_t* offsets, int T,
+                        float* y_perm, hipStream_t s);
+int smoe_launch_ffn_bf16(const smoe_layer* L, const uint16_t* x_perm, const int32_t* offsets, int T,
+                         uint16_t* y_perm, hipStream_t s);
+int smoe_launch_combine(const smoe_layer* L, const void* y_perm, const int32_t* inv_perm,
+                        const float* gate, const void* residual, int T, void* out, hipStream_t s);
+int smoe_launch_load_slot(const smoe_layer* L, int slot, int expert, int old_expert,
+                          const void* w1_src, const void* w2_src, hipStream_t s);
+int smoe_launch_expert_norm(const smoe_layer* L, const void* w1, const void* w2, int n, float* out,
+                            hipStream_t s);
+int smoe_launch_clear_maps(const smoe_layer* L, hipStream_t s);
+
+// bf16 <-> fp32 on the device.  Widening is exact; narrowing rounds to
+// nearest, ties to even (inputs are finite by contract).
+__device__ __forceinline__ float smoe_bf16_to_f32(uint16_t b) {
+    return __uint_as_float((uint32_t)b << 16);
+}
+__device__ __forceinline__ uint16_t smoe_f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}

@@ -1,0 +1,108 @@
+"""Host-side tests of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, and rejects bad arguments before any launch."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2308_15030_amd import binding as b
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000          # a non-null, 256-byte aligned "device pointer" that is never dereferenced
+
+
+def test_exports_match_header():
+    text = open(os.path.join(ROOT, "include", "swapmoe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(smoe_[a-z_]+)\s*\(", text))
+    assert declared == set(b.EXPORTS)
+    lib = C.CDLL(b.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    for six in ("smoe_route", "smoe_importance", "smoe_permute", "smoe_expert_ffn", "smoe_combine",
+                "smoe_set_resident"):
+        assert six in declared
+
+
+def _status(fn, *a):
+    with pytest.raises(b.SmoeError) as e:
+        fn(*a)
+    assert b.smoe_last_error() != ""
+    return e.value.status
+
+
+def test_create_validation():
+    ok = dict(E=8, K=2, d_model=64, d_ff=256, max_tokens=256, dtype=b.SMOE_F32)
+    h = b.smoe_create(**ok)
+    assert b.smoe_workspace_bytes(h) > 256 * 256 * 4
+    assert b.smoe_slot_weight_bytes(h) == 2 * 64 * 256 * 4
+    b.smoe_destroy(h)
+    for bad in (dict(E=0), dict(E=257), dict(K=0), dict(K=9), dict(d_model=0), dict(d_ff=-4),
+                dict(max_tokens=0), dict(dtype=7), dict(gate_mode=2), dict(d_model=66),
+                dict(dtype=b.SMOE_BF16, d_model=48)):
+        assert _status(lambda kw: b.smoe_create(**kw), {**ok, **bad}) == b.SMOE_EINVAL
+    assert b._lib.smoe_create(None, None) == b.SMOE_EINVAL
+    assert b._lib.smoe_destroy(None) == b.SMOE_EINVAL
+    assert b.smoe_workspace_bytes(None) == 0
+
+
+def test_workspace_grows_with_tokens():
+    a = b.smoe_create(64, 16, 768, 3072, 4096, b.SMOE_BF16)
+    c = b.smoe_create(64, 16, 768, 3072, 8192, b.SMOE_BF16)
+    assert b.smoe_workspace_bytes(c) > b.smoe_workspace_bytes(a) >= 4096 * 3072 * 2
+    assert b.smoe_slot_weight_bytes(a) == 16 * 768 * 3072 * 2
+    b.smoe_destroy(a); b.smoe_destroy(c)
+
+
+def test_state_and_argument_errors_before_any_launch():
+    h = b.smoe_create(8, 2, 64, 256, 128, b.SMOE_F32)
+    lib = b._lib
+    # nothing bound yet
+    assert lib.smoe_route(h, FAKE, 4, FAKE, FAKE, FAKE, FAKE, FAKE, None) == b.SMOE_ESTATE
+    assert lib.smoe_set_resident(h, 0, 0, FAKE, FAKE, None) == b.SMOE_ESTATE
+    # bind: nulls and alignment
+    assert lib.smoe_bind(h, None, FAKE, FAKE, FAKE, FAKE) == b.SMOE_EINVAL
+    assert lib.smoe_bind(h, FAKE, FAKE + 64, FAKE, FAKE, FAKE) == b.SMOE_EINVAL
+    assert lib.smoe_bind(h, FAKE, FAKE, FAKE, FAKE, FAKE) == b.SMOE_OK
+    # set_resident ranges
+    assert lib.smoe_set_resident(h, -1, 0, FAKE, FAKE, None) == b.SMOE_EINVAL
+    assert lib.smoe_set_resident(h, 2, 0, FAKE, FAKE, None) == b.SMOE_EINVAL
+    assert lib.smoe_set_resident(h, 0, 8, FAKE, FAKE, None) == b.SMOE_EINVAL
+    assert lib.smoe_set_resident(h, 0, 0, None, FAKE, None) == b.SMOE_EINVAL
+    assert "null" in b.smoe_last_error()
+    # slots not all filled -> route / ffn refuse; T range is checked first
+    assert lib.smoe_route(h, FAKE, 129, FAKE, FAKE, FAKE, FAKE, FAKE, None) == b.SMOE_EINVAL
+    assert lib.smoe_route(h, FAKE, -1, FAKE, FAKE, FAKE, FAKE, FAKE, None) == b.SMOE_EINVAL
+    assert lib.smoe_route(h, FAKE, 4, FAKE, FAKE, FAKE, FAKE, FAKE, None) == b.SMOE_ESTATE
+    assert lib.smoe_expert_ffn(h, FAKE, FAKE, 4, FAKE, None) == b.SMOE_ESTATE
+    assert "slots" in b.smoe_last_error()
+    # null buffers and flags on the calls that do not need a full resident set
+    assert lib.smoe_importance(h, None, FAKE, FAKE, 4, FAKE, FAKE, FAKE, 0, None) == b.SMOE_EINVAL
+    assert lib.smoe_importance(h, FAKE, FAKE, FAKE, 4, FAKE, FAKE, FAKE, 2, None) == b.SMOE_EINVAL
+    assert lib.smoe_importance(h, FAKE, FAKE, FAKE, 4, None, FAKE, FAKE, 0, None) == b.SMOE_EINVAL
+    assert lib.smoe_permute(h, FAKE, None, 4, FAKE, FAKE, FAKE, FAKE, None) == b.SMOE_EINVAL
+    assert lib.smoe_permute(h, FAKE, FAKE, 4, FAKE, FAKE, FAKE, None, None) == b.SMOE_EINVAL
+    assert lib.smoe_permute(h, FAKE + 4, FAKE, 4, FAKE, FAKE, FAKE, FAKE, None) == b.SMOE_EINVAL
+    assert lib.smoe_combine(h, FAKE, FAKE, None, None, 4, FAKE, None) == b.SMOE_EINVAL
+    assert lib.smoe_combine(h, FAKE, FAKE, FAKE, None, 999, FAKE, None) == b.SMOE_EINVAL
+    # legal no-ops
+    assert lib.smoe_combine(h, None, None, None, None, 0, None, None) == b.SMOE_OK
+    assert lib.smoe_importance(h, None, None, None, 0, FAKE, FAKE, FAKE, 1, None) == b.SMOE_OK
+    assert lib.smoe_route(None, FAKE, 4, FAKE, FAKE, FAKE, FAKE, FAKE, None) == b.SMOE_EINVAL
+    b.smoe_destroy(h)
+
+
+def test_maps_and_policy_on_host():
+    h = b.smoe_create(6, 3, 64, 64, 16, b.SMOE_F32)
+    s2e = np.zeros(3, np.int32); e2s = np.zeros(6, np.int32)
+    b.smoe_get_maps(h, s2e, e2s)
+    assert (s2e == -1).all() and (e2s == -1).all()
+    # empty slots: the three best experts fill slots 0,1,2 in descending score order
+    score = np.array([0.1, 0.9, 0.3, 0.9, 0.0, 0.5], np.float32)
+    cs = np.empty(3, np.int32); ce = np.empty(3, np.int32)
+    n = b.smoe_select_resident(h, score, cs, ce)
+    assert n == 3 and cs.tolist() == [0, 1, 2] and ce.tolist() == [1, 3, 5]
+    assert b._lib.smoe_select_resident(h, None, cs.ctypes.data, ce.ctypes.data) == b.SMOE_EINVAL
+    b.smoe_destroy(h)

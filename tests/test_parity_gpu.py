@@ -1,0 +1,186 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle, element by
+element, on the same seeded inputs.
+
+Each call is teacher-forced (it receives the ORACLE's outputs of the previous
+step), so integer results are comparable bit for bit; a chained run of the
+whole layer is checked at the end-to-end tolerance.
+
+Tolerances (max-abs-relative = max|got-ref| / max|ref| over the tensor):
+  fp32 path outputs 1e-4, bf16 path outputs 2e-2 (hidden activations and
+  outputs are rounded to bf16, 2^-8 relative each; the oracle rounds once);
+  gates and norms 1e-5 elementwise (fp32 sums of <= 1024 terms); importance
+  sums 1e-4 per expert; every index, count and permutation bit-exact.  Routing
+  indices are compared on tokens whose top-1/top-2 logit gap exceeds
+  1e-4 * max(1, max|logit|) (oracle.MARGIN): below that an fp32 logit may
+  legitimately order two experts differently from the fp64 oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2308_15030_amd import workloads as wl
+from harness import Case, max_abs_rel, to_dev, to_host, values
+
+pytestmark = pytest.mark.gpu
+
+TOL_OUT = {wl.F32: 1e-4, wl.BF16: 2e-2}
+TOL_GATE = 1e-5
+TOL_SCORE = 1e-4
+
+
+def small_cfg(name, **kw):
+    base = dict(E=8, K=3, d_model=96, d_ff=160, T=300, dtype=wl.BF16, seed=11)
+    base.update(kw)
+    return wl.MoEConfig(name, **base)
+
+
+CASES = {
+    "c1": dict(cfg=wl.CONFIGS["c1"]),
+    # several token tiles per slot, ragged tails, feature counts that do not fill a workgroup tile
+    "ragged-bf16": dict(cfg=small_cfg("ragged-bf16"), resident=[5, 0, 6], router_scale=20.0),
+    "ragged-fp32": dict(cfg=small_cfg("ragged-fp32", dtype=wl.F32, d_model=52, d_ff=100, T=131),
+                        resident=[2, 7, 4], router_scale=20.0),
+    "one-slot": dict(cfg=small_cfg("one-slot", K=1, T=77), resident=[3], router_scale=20.0),
+    "all-resident": dict(cfg=small_cfg("all-resident", E=4, K=4, T=513, d_model=64, d_ff=64),
+                         resident=[2, 0, 3, 1], router_scale=20.0),
+    "renorm": dict(cfg=small_cfg("renorm", T=200), resident=[1, 2, 3], gate_mode=1, router_scale=20.0),
+    "wide-E": dict(cfg=small_cfg("wide-E", E=200, K=20, T=1500, d_model=64, d_ff=96), router_scale=20.0),
+    "c2": dict(cfg=wl.CONFIGS["c2"]),
+    "c3-layer0": dict(cfg=wl.CONFIGS["c3"], layer=0),
+    "c3-layer5": dict(cfg=wl.CONFIGS["c3"], layer=5),
+}
+
+
+@pytest.fixture(scope="module", params=list(CASES))
+def case(request):
+    kw = dict(CASES[request.param])
+    print(f"[case {request.param}] building", flush=True)
+    c = Case(**kw)
+    c.name = request.param
+    c.ref = oracle.layer_forward(c.x, c.Wr, *c.slot_weights_host(), c.e2s, c.gate_mode)
+    yield c
+    c.L.close()
+
+
+def test_expert_norm(case):
+    got = to_host(case.L.expert_norm)[case.bank_ids]
+    np.testing.assert_allclose(got, case.en_oracle[case.bank_ids], rtol=1e-5)
+
+
+def test_route(case):
+    c, L, r = case, case.L, case.ref
+    L.route(c.d_x, c.T)
+    torch.cuda.synchronize()
+    ok = ~r["ambiguous"]
+    assert ok.mean() > 0.98, "margin excludes too many tokens for the test to mean anything"
+    assert np.array_equal(to_host(L.orig_expert)[ok], r["orig_expert"][ok])
+    assert np.array_equal(to_host(L.slot)[ok], r["slot"][ok])
+    s2e, e2s = L.maps()
+    assert np.array_equal(s2e, c.s2e) and np.array_equal(e2s, c.e2s)
+    assert np.isin(to_host(L.slot), np.arange(c.cfg.K)).all()        # every token is served by a slot
+    np.testing.assert_allclose(to_host(L.orig_gate)[ok], r["orig_gate"][ok], rtol=TOL_GATE)
+    np.testing.assert_allclose(to_host(L.gate)[ok], r["gate"][ok], rtol=TOL_GATE)
+    np.testing.assert_allclose(to_host(L.xnorm), r["xnorm"], rtol=TOL_GATE)
+    # ambiguous tokens must still pick one of the two near-tied experts
+    amb = np.nonzero(~ok)[0]
+    for t in amb:
+        lg = r["logits"][t]
+        assert lg[to_host(L.orig_expert)[t]] >= lg.max() - oracle.MARGIN * max(1.0, np.abs(lg).max())
+
+
+def test_importance(case):
+    c, L, r = case, case.L, case.ref
+    L.orig_expert.copy_(to_dev(r["orig_expert"])); L.orig_gate.copy_(to_dev(r["orig_gate"]))
+    L.xnorm.copy_(to_dev(r["xnorm"]))
+    st = oracle.importance(r["orig_expert"], r["orig_gate"], r["xnorm"], c.en_oracle)
+    L.importance(c.T, accumulate=0)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(L.count), st[0])
+    np.testing.assert_allclose(to_host(L.gsum), st[1], rtol=TOL_SCORE, atol=1e-30)
+    np.testing.assert_allclose(to_host(L.score), st[2], rtol=TOL_SCORE, atol=1e-30)
+    assert int(to_host(L.count).sum()) == c.T
+    first = [to_host(L.gsum).copy(), to_host(L.score).copy()]
+    L.importance(c.T, accumulate=1)
+    L.importance(c.T, accumulate=1)
+    torch.cuda.synchronize()
+    st3 = oracle.importance(r["orig_expert"], r["orig_gate"], r["xnorm"], c.en_oracle,
+                            state=oracle.importance(r["orig_expert"], r["orig_gate"], r["xnorm"],
+                                                    c.en_oracle, state=st))
+    assert np.array_equal(to_host(L.count), st3[0])
+    np.testing.assert_allclose(to_host(L.score), st3[2], rtol=TOL_SCORE, atol=1e-30)
+    # deterministic: overwrite mode reproduces the first result bit for bit
+    L.importance(c.T, accumulate=0)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(L.gsum), first[0]) and np.array_equal(to_host(L.score), first[1])
+
+
+def test_permute(case):
+    c, L, r = case, case.L, case.ref
+    L.slot.copy_(to_dev(r["slot"]))
+    L.permute(c.d_x, c.T)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(L.offsets), r["offsets"])
+    assert np.array_equal(to_host(L.perm), r["perm"])
+    assert np.array_equal(to_host(L.inv_perm), r["inv_perm"])
+    assert np.array_equal(to_host(L.x_perm), r["x_perm"])
+
+
+def test_expert_ffn(case):
+    c, L, r = case, case.L, case.ref
+    L.x_perm.copy_(to_dev(r["x_perm"])); L.offsets.copy_(to_dev(r["offsets"]))
+    L.y_perm.fill_(0)
+    L.expert_ffn(c.T)
+    torch.cuda.synchronize()
+    got = values(to_host(L.y_perm), c.cfg.dtype)
+    err = max_abs_rel(got, r["y_perm"])
+    print(f"[{c.name}] ffn max-abs-rel {err:.3e}", flush=True)
+    assert err <= TOL_OUT[c.cfg.dtype]
+    # per-segment as well, so a small segment cannot hide behind a large one's scale
+    for k in range(c.cfg.K):
+        a, b_ = r["offsets"][k], r["offsets"][k + 1]
+        if b_ > a:
+            assert max_abs_rel(got[a:b_], r["y_perm"][a:b_]) <= TOL_OUT[c.cfg.dtype]
+
+
+def test_combine(case):
+    c, L, r = case, case.L, case.ref
+    dt = c.cfg.dtype
+    y_in = r["y_perm"].astype(np.float32) if dt == wl.F32 else oracle.round_bf16(r["y_perm"])
+    L.y_perm.copy_(to_dev(y_in)); L.inv_perm.copy_(to_dev(r["inv_perm"])); L.gate.copy_(to_dev(r["gate"]))
+    L.combine(c.T)
+    torch.cuda.synchronize()
+    ref = oracle.combine(y_in, r["inv_perm"], r["gate"], dt)
+    got, refv = values(to_host(L.out), dt), values(ref, dt)
+    # one fp32 product then one rounding: at most one unit in the last place of the storage type
+    ulp = 2.0 ** -23 if dt == wl.F32 else 2.0 ** -7
+    assert (np.abs(got - refv) <= ulp * np.abs(refv) + 1e-38).all()
+    assert (got == refv).mean() > 0.99
+    # with a residual stream
+    res = to_dev(c.x)
+    L.combine(c.T, residual=res)
+    torch.cuda.synchronize()
+    ref = values(oracle.combine(y_in, r["inv_perm"], r["gate"], dt, residual=c.x), dt)
+    got = values(to_host(L.out), dt)
+    assert max_abs_rel(got, ref) <= (1e-6 if dt == wl.F32 else 2.0 ** -7)
+
+
+def test_whole_layer_chained(case):
+    """Free-running: each call consumes the previous call's DEVICE output."""
+    c, L, r = case, case.L, case.ref
+    out = L.forward(c.d_x, c.T, accumulate=0)
+    torch.cuda.synchronize()
+    ok = ~r["ambiguous"]
+    got = values(to_host(out), c.cfg.dtype)
+    ref = values(r["out"], c.cfg.dtype)
+    err = max_abs_rel(got[ok], ref[ok])
+    print(f"[{c.name}] layer max-abs-rel {err:.3e}", flush=True)
+    assert err <= TOL_OUT[c.cfg.dtype]
+    assert int(to_host(L.offsets)[-1]) == c.T
+    assert np.array_equal(np.sort(to_host(L.perm)), np.arange(c.T))
+    # run it again: integer outputs identical, float outputs bitwise identical (no atomics anywhere)
+    snap = [to_host(t).copy() for t in (L.perm, L.offsets, L.out, L.score)]
+    L.forward(c.d_x, c.T, accumulate=0)
+    torch.cuda.synchronize()
+    for a, t in zip(snap, (L.perm, L.offsets, L.out, L.score)):
+        assert np.array_equal(a, to_host(t))
