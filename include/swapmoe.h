@@ -169,6 +169,14 @@ int smoe_permute(smoe_layer_t* layer, const void* x, const int32_t* slot, int T,
 int smoe_expert_ffn(smoe_layer_t* layer, const void* x_perm, const int32_t* offsets, int T,
                     void* y_perm, void* stream);
 
+/* Measurement aid (not part of the paper's method): HIP events the NEXT
+ * smoe_expert_ffn call on this handle records on its stream -- ev_begin before
+ * the first product, ev_mid between the two products, ev_end after the second
+ * -- so each kernel's duration can be read with hipEventElapsedTime.  The
+ * events are caller-owned hipEvent_t values passed as void*; they are used
+ * once and then forgotten.  Pass three NULLs to cancel. */
+int smoe_set_profile_events(smoe_layer_t* layer, void* ev_begin, void* ev_mid, void* ev_end);
+
 /* Gate-weighted combine, y = G(x)_i E_i(x) in token order:
  *   out[t, :] = gate[t] * y_perm[inv_perm[t], :]  (+ residual[t, :] if not NULL)
  * computed in fp32 and rounded once to the layer's dtype. */

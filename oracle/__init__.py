@@ -36,6 +36,7 @@ def lib():
         _lib.oracle_combine.restype = C.c_int
         _lib.oracle_select_resident.restype = C.c_int
         _lib.oracle_round_bf16.restype = None
+        _lib.oracle_num_threads.restype = C.c_int
     return _lib
 
 
@@ -169,6 +170,10 @@ def select_resident(score, slot_to_expert, expert_to_slot):
     if n < 0:
         raise ValueError(f"oracle_select_resident rc={n}")
     return s2e, e2s, [(int(cs[i]), int(ce[i])) for i in range(n)]
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
 
 
 def round_bf16(a):

@@ -34,6 +34,9 @@
 #include <vector>
 #include <algorithm>
 #include <limits>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 namespace {
 
@@ -323,6 +326,15 @@ int oracle_select_resident(const double* score, int E, int K, int32_t* slot_to_e
         ++n;
     }
     return n;
+}
+
+// Threads the row loops will use (reported next to the oracle's timings).
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
 }
 
 // Round-to-nearest-even double -> bf16 bit patterns (exposed for the tests).

@@ -51,6 +51,7 @@ _SIGS = {
     "smoe_permute": (C.c_int, [_vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp]),
     "smoe_expert_ffn": (C.c_int, [_vp, _vp, _vp, _i, _vp, _vp]),
     "smoe_combine": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _i, _vp, _vp]),
+    "smoe_set_profile_events": (C.c_int, [_vp, _vp, _vp, _vp]),
 }
 EXPORTS = tuple(_SIGS)
 for _name, (_res, _args) in _SIGS.items():
@@ -150,6 +151,17 @@ def smoe_expert_ffn(layer, x_perm, offsets, T, y_perm, stream=None):
 def smoe_combine(layer, y_perm, inv_perm, gate, residual, T, out, stream=None):
     _check(_lib.smoe_combine(layer, _ptr(y_perm), _ptr(inv_perm), _ptr(gate), _ptr(residual), T,
                              _ptr(out), _stream(stream)))
+
+
+def smoe_set_profile_events(layer, ev_begin, ev_mid, ev_end):
+    """Events are torch.cuda.Event(enable_timing=True) objects (or None)."""
+    def h(e):
+        if e is None:
+            return None
+        if e.cuda_event == 0:      # torch creates the HIP event lazily, on first record
+            e.record()
+        return e.cuda_event
+    _check(_lib.smoe_set_profile_events(layer, h(ev_begin), h(ev_mid), h(ev_end)))
 
 
 # ---------------------------------------------------------------------------

@@ -254,8 +254,21 @@ int smoe_expert_ffn(smoe_layer_t* L, const void* x_perm, const int32_t* offsets,
     if (misaligned(x_perm, 16) || misaligned(y_perm, 16))
         return smoe_fail(SMOE_EINVAL, "smoe_expert_ffn: x_perm and y_perm must be 16-byte aligned");
     if (L->cfg.dtype == SMOE_F32)
-        return smoe_launch_ffn_f32(L, (const float*)x_perm, offsets, T, (float*)y_perm, as_stream(stream));
-    return smoe_launch_ffn_bf16(L, (const uint16_t*)x_perm, offsets, T, (uint16_t*)y_perm, as_stream(stream));
+        rc = smoe_launch_ffn_f32(L, (const float*)x_perm, offsets, T, (float*)y_perm, as_stream(stream));
+    else
+        rc = smoe_launch_ffn_bf16(L, (const uint16_t*)x_perm, offsets, T, (uint16_t*)y_perm, as_stream(stream));
+    L->prof_ev[0] = L->prof_ev[1] = L->prof_ev[2] = nullptr;
+    return rc;
+}
+
+int smoe_set_profile_events(smoe_layer_t* L, void* ev_begin, void* ev_mid, void* ev_end) {
+    if (!L) return smoe_fail(SMOE_EINVAL, "smoe_set_profile_events: null handle");
+    bool none = !ev_begin && !ev_mid && !ev_end, all = ev_begin && ev_mid && ev_end;
+    if (!none && !all) return smoe_fail(SMOE_EINVAL, "smoe_set_profile_events: pass three events or three NULLs");
+    L->prof_ev[0] = (hipEvent_t)ev_begin;
+    L->prof_ev[1] = (hipEvent_t)ev_mid;
+    L->prof_ev[2] = (hipEvent_t)ev_end;
+    return SMOE_OK;
 }
 
 int smoe_combine(smoe_layer_t* L, const void* y_perm, const int32_t* inv_perm, const float* gate,

@@ -224,7 +224,10 @@ int smoe_launch_ffn_bf16(const smoe_layer* L, const uint16_t* x_perm, const int3
     int v1, v2;
     pick_variants(c, T, v1, v2);
     uint16_t* h = (uint16_t*)L->d_hidden;
+    if (L->prof_ev[0]) (void)hipEventRecord(L->prof_ev[0], s);
     launch_variant<true>(v1, x_perm, L->slot_w1, offsets, c.K, h, c.d_model, c.d_ff, T, s);
+    if (L->prof_ev[1]) (void)hipEventRecord(L->prof_ev[1], s);
     launch_variant<false>(v2, h, L->slot_w2, offsets, c.K, y_perm, c.d_ff, c.d_model, T, s);
+    if (L->prof_ev[2]) (void)hipEventRecord(L->prof_ev[2], s);
     return smoe_check_hip(hipGetLastError(), "smoe_expert_ffn launch");
 }

@@ -33,6 +33,8 @@ struct smoe_layer {
     int32_t* d_sort_hist = nullptr;          // [sort blocks, K]
     void* d_hidden = nullptr;                // [max_tokens, d_ff] activations of the FFN
     float* d_partial = nullptr;              // small-T FFN: split partial sums
+
+    hipEvent_t prof_ev[3] = {nullptr, nullptr, nullptr};   // one-shot FFN profiling events
 };
 
 struct smoe_ws_layout {
