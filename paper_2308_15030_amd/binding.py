@@ -15,7 +15,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libswapmoe.so")
+# SMOE_LIBRARY points at another build of the same library (e.g. an instrumented one)
+LIB_PATH = os.environ.get("SMOE_LIBRARY") or os.path.join(_HERE, "libswapmoe.so")
 
 SMOE_OK, SMOE_EINVAL, SMOE_ESTATE, SMOE_EHIP, SMOE_ENOMEM = 0, -1, -2, -3, -4
 SMOE_F32, SMOE_BF16 = 0, 1

@@ -40,7 +40,8 @@ smoe_ws_layout smoe_ws_plan(const smoe_config& c) {
     w.e2s = off;     off = align_up(off + (size_t)c.E * 4, 256);
     w.s2e = off;     off = align_up(off + (size_t)c.K * 4, 256);
     w.hist = off;    off = align_up(off + (size_t)smoe_sort_blocks(c.max_tokens) * c.K * 4, 256);
-    w.hidden = off;  off = align_up(off + (size_t)c.max_tokens * c.d_ff * smoe_elem_size(c.dtype), 256);
+    // hidden activations: every segment is re-based to a multiple of 32 rows
+    w.hidden = off;  off = align_up(off + ((size_t)c.max_tokens + 32 * (size_t)c.K) * c.d_ff * smoe_elem_size(c.dtype), 256);
     w.partial = off; off = align_up(off, 256);
     w.total = off;
     return w;

@@ -7,21 +7,28 @@
 // Shape of one GEMM:  Y[T, N] = act(X[T, R] . B_k[R, N])  for the rows of slot k.
 //
 // The weights are the MFMA's first operand and the tokens its second, so an
-// accumulator lane ends up holding 4 consecutive output features of ONE token
-// and stores them as one 8-byte word; and the token operand (8 consecutive
-// reduction elements of one row) is contiguous in the row-major activations.
+// accumulator lane ends up holding 4 consecutive output features of ONE token,
+// and the token operand is 8 consecutive reduction elements of one row.
 //
 // Weights arrive in fragment order (see resident.hip): every wave streams its
 // own feature blocks straight from HBM into registers with contiguous 1-KiB
-// loads, prefetched one 64-deep reduction slice ahead -- they never touch LDS,
-// since no other wave of the workgroup needs them.  The token tile is what the
-// waves share; it is staged through a double-buffered, padded LDS tile.
+// loads, prefetched PD reduction slices ahead in a register ring -- they never
+// touch LDS, since no other wave of the workgroup needs them.  The token tile
+// is what the waves share; it is staged through a double-buffered LDS tile.
 //
-// Workgroup = NW waves; tile = (32*BFR tokens) x (NW*AF*32 features); wave w
-// owns AF feature blocks and all BFR token blocks: AF*BFR accumulators of 16
-// VGPRs.  Token tiles are enumerated per slot from the device-side offsets.
+// The hidden activations h never leave the library, so they are kept in
+// fragment order too: rows are re-based per segment to a multiple of 32
+// ("padded rows"), and h is stored as 16-byte units [row/32][feature/8][row%32]
+// of 8 features.  The first GEMM's accumulator layout then stores straight into
+// 512-byte runs, and the second GEMM stages its token tile with a linear copy
+// and reads operands from LDS without padding or bank conflicts.
+//
+// Workgroup = NW waves; tile = (32*MAXB tokens) x (NW*AF*32 features); wave w
+// owns AF feature blocks and all token blocks: AF*NBF accumulators of 16 VGPRs.
+// Token tiles are enumerated per slot from the device-side offsets.
 
 #include <cstdlib>
+#include <type_traits>
 
 #include "smoe_internal.h"
 
@@ -30,17 +37,52 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int BK = 64;             // reduction slice per LDS stage
-constexpr int KS = BK / 16;        // MFMA steps per slice
-constexpr int LDR = BK + 8;        // LDS row pitch in bf16: 144 B, conflict-free b128 reads
+constexpr int KPAD = 8;   // row-major token tile: LDS pitch (BKT+8)*2 B keeps b128 reads conflict-free
 
-__device__ __forceinline__ bool find_tile(const int32_t* __restrict__ offsets, int nslots, int T, int mt,
-                                          int bt, int& slot, int& m0, int& m_end) {
+constexpr int XCDS = 8;   // MI355X: 8 accelerator dies, each with a private L2
+
+// Work item of workgroup `wg`.  A work item is (row tile, feature tile); the
+// row tiles of all slots form one list in slot order, ceil(len/bt) per slot.
+// Workgroups are dealt to the 8 XCDs round-robin by their linear id, so
+// workgroup wg runs on XCD wg % 8 as that die's (wg / 8)-th workgroup.  Die x
+// owns the x-th eighth of the row-tile list (a contiguous run, so it touches
+// few slots) and ALL feature tiles of those rows: activations are pulled
+// through exactly one L2, and a slot's weights through as few L2s as its rows
+// span.  On a die the row tile varies fastest, so workgroups that run together
+// share weight tiles and keep the die's activations L2-resident.
+// Returns false when the die has fewer items than wg / 8.
+// Outputs: slot, feature tile, first row m0, segment end m_end, and pm0 = the
+// padded row (segments re-based to multiples of 32) that m0 maps to.
+__device__ __forceinline__ bool find_item(const int32_t* __restrict__ offsets, int nslots, int T, int bt,
+                                          int ftiles, int wg, int& slot, int& ftile, int& m0, int& m_end,
+                                          int& pm0) {
+    int total = 0;
+    {
+        int a = min(max(offsets[0], 0), T);                 // clamps guard misuse
+        for (int k = 0; k < nslots; ++k) {
+            int b = min(max(offsets[k + 1], a), T);
+            total += (b - a + bt - 1) / bt;
+            a = b;
+        }
+    }
+    const int die = wg % XCDS, j = wg / XCDS;
+    const int lo = (int)((long long)total * die / XCDS), hi = (int)((long long)total * (die + 1) / XCDS);
+    const int cnt = hi - lo;
+    if (cnt <= 0 || j >= cnt * ftiles) return false;
+    ftile = j / cnt;
+    int mt = lo + j % cnt;                                  // index into the global row-tile list
+    int pbase = 0;
+    int a = min(max(offsets[0], 0), T);
     for (int k = 0; k < nslots; ++k) {
-        int a = min(max(offsets[k], 0), T), b = min(max(offsets[k + 1], a), T);   // clamp guards misuse
+        int b = min(max(offsets[k + 1], a), T);
         int tiles = (b - a + bt - 1) / bt;
-        if (mt < tiles) { slot = k; m0 = a + mt * bt; m_end = b; return true; }
+        if (mt < tiles) {
+            slot = k; m0 = a + mt * bt; m_end = b; pm0 = pbase + mt * bt;
+            return true;
+        }
         mt -= tiles;
+        pbase += (b - a + 31) & ~31;
+        a = b;
     }
     return false;
 }
@@ -51,105 +93,147 @@ __device__ __forceinline__ bf16x8 as_frag(uint4 v) {
     return c.b;
 }
 
-template <int AF, int BFR, int NW, bool RELU>
-__global__ __launch_bounds__(NW * 64) void grouped_gemm_bf16(
-    const uint16_t* __restrict__ X, const uint4* __restrict__ Wp, const int32_t* __restrict__ offsets,
-    int nslots, int T, uint16_t* __restrict__ Y, int R, int N) {
-    constexpr int BT = 32 * BFR;
+// One workgroup tile with NBF live token blocks.  Everything is compile-time
+// shaped: no branch inside the reduction loop.
+//   AF    feature blocks per wave          NW    waves per workgroup
+//   BKT   reduction slice per LDS stage    PD    weight prefetch distance in slices
+//   XFRAG token operand X is in fragment order (else row-major [T, R])
+//   YFRAG output Y is written in fragment order (else row-major [T, N])
+template <int AF, int NBF, int NW, int BKT, int PD, bool XFRAG, bool YFRAG, bool RELU>
+__device__ __forceinline__ void run_tile(const uint16_t* __restrict__ X, const uint4* __restrict__ Wp,
+                                         uint16_t* __restrict__ Y, int R, int N, int slot, int m0,
+                                         int m_end, int pm0, int ftile, uint16_t* xs, int stage_elems) {
     constexpr int THREADS = NW * 64;
-    constexpr int CPT = BT * (BK / 8) / THREADS;      // 16-byte chunks of the token tile per thread
-    static_assert(BT * (BK / 8) % THREADS == 0, "token tile must split evenly over the threads");
-    __shared__ __align__(16) uint16_t xs[2][BT * LDR];
+    constexpr int KS = BKT / 16;
+    constexpr int LDR = BKT + KPAD;
+    constexpr int CPR = BKT / 8;                          // 16-byte pieces per token row and slice
+    constexpr int PIECES = 32 * NBF * CPR;                // pieces of the token tile per slice
+    constexpr int CPT = (PIECES + THREADS - 1) / THREADS;
 
-    int slot, m0, m_end;
-    if (!find_tile(offsets, nslots, T, blockIdx.x, BT, slot, m0, m_end)) return;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int nfb = N >> 5;                           // 32-feature blocks in B
-    const int nrb = R >> 4;                           // 16-deep reduction blocks in B
-    const int fb0 = (blockIdx.y * NW + wave) * AF;
-    const int nbf = min(BFR, (m_end - m0 + 31) >> 5); // token blocks that hold real rows
-    const int nchunks = (R + BK - 1) / BK;
+    const int nfb = N >> 5, nrb = R >> 4;
+    const int fb0 = (ftile * NW + wave) * AF;
+    const int nchunks = R / BKT;
 
-    // per-feature-block base of this lane's 16-byte units (clamped: surplus blocks
-    // recompute the last one and are not stored)
     const uint4* wbase[AF];
 #pragma unroll
     for (int a = 0; a < AF; ++a) {
-        int fb = min(fb0 + a, nfb - 1);
+        int fb = min(fb0 + a, nfb - 1);                   // surplus blocks recompute the last one, unstored
         wbase[a] = Wp + ((size_t)slot * nfb + fb) * nrb * 64 + lane;
     }
+    // this thread's pieces of the token tile: global source, its stride per slice, LDS destination
+    const uint16_t* tsrc[CPT];
+    int tdst[CPT];
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+        int idx = min(tid + i * THREADS, PIECES - 1);     // surplus threads repeat the last piece
+        if (XFRAG) {
+            int b = idx / (CPR * 32), j = (idx / 32) % CPR, t = idx % 32;
+            tsrc[i] = X + (((size_t)((pm0 >> 5) + b) * (R >> 3) + j) * 32 + t) * 8;
+            tdst[i] = idx * 8;
+        } else {
+            int r = idx / CPR, c = idx % CPR;
+            tsrc[i] = X + (size_t)min(m0 + r, m_end - 1) * R + c * 8;
+            tdst[i] = r * LDR + c * 8;
+        }
+    }
+    const size_t tstep = XFRAG ? (size_t)CPR * 32 * 8 : (size_t)BKT;     // elements per slice
+    // this lane's operand inside token block 0, reduction step 0; per block / per step strides
+    const int xoff = XFRAG ? ((lane >> 5) * 32 + (lane & 31)) * 8 : (lane & 31) * LDR + (lane >> 5) * 8;
+    constexpr int XB = XFRAG ? CPR * 32 * 8 : 32 * LDR;   // token block stride in LDS
+    constexpr int XK = XFRAG ? 2 * 32 * 8 : 16;           // reduction step stride in LDS
 
-    f32x16 acc[AF][BFR];
+    f32x16 acc[AF][NBF];
 #pragma unroll
     for (int a = 0; a < AF; ++a)
 #pragma unroll
-        for (int b = 0; b < BFR; ++b)
+        for (int b = 0; b < NBF; ++b)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-    uint4 treg[CPT];
-    uint4 wcur[KS][AF], wnext[KS][AF];
-
-    auto load_tokens = [&](int chunk) {
+    // Software pipeline.  Weights: a ring of PD+1 slices in registers, loaded PD
+    // slices ahead; tokens: two register sets, loaded TWO slices ahead and
+    // copied into the LDS double buffer one slice ahead, so every global load
+    // has at least a full slice of MFMA work to land; operands: the next
+    // reduction step's LDS reads are issued before the current step's MFMAs.
+    // Loads past the last slice are clamped to it (fetched again, never used)
+    // so the loop body has no conditional loads.  With PD = 0 (odd slice
+    // counts) the token distance drops to one slice.
+    constexpr int TD = (PD & 1) ? 2 : 1;
+    uint4 tregA[CPT], tregB[CPT];                       // token register sets 0 and 1
+    uint4 wbuf[PD + 1][KS][AF];
 #pragma unroll
-        for (int i = 0; i < CPT; ++i) {
-            int idx = tid + i * THREADS;
-            int r = idx >> 3, c = idx & 7;
-            int row = min(m0 + r, m_end - 1);
-            int col = chunk * BK + c * 8;
-            treg[i] = col < R ? *(const uint4*)&X[(size_t)row * R + col] : make_uint4(0, 0, 0, 0);
-        }
-    };
-    auto store_tokens = [&](int stage) {
+    for (int i = 0; i < CPT; ++i) tregA[i] = *(const uint4*)tsrc[i];
 #pragma unroll
-        for (int i = 0; i < CPT; ++i) {
-            int idx = tid + i * THREADS;
-            int r = idx >> 3, c = idx & 7;
-            *(uint4*)&xs[stage][r * LDR + c * 8] = treg[i];
-        }
-    };
-    auto load_weights = [&](int chunk, uint4 (&w)[KS][AF]) {
+    for (int p = 0; p < PD; ++p) {
+        const int cp = min(p, nchunks - 1);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            int rb = min(chunk * KS + ks, nrb - 1);   // past the end: tokens there are zero
+        for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-            for (int a = 0; a < AF; ++a) w[ks][a] = wbase[a][(size_t)rb * 64];
-        }
-    };
-
-    load_tokens(0);
-    load_weights(0, wcur);
-    store_tokens(0);
+            for (int a = 0; a < AF; ++a) wbuf[p][ks][a] = wbase[a][(size_t)(cp * KS + ks) * 64];
+    }
+    if (TD == 2) {
+        const int c1 = min(1, nchunks - 1);
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) tregB[i] = *(const uint4*)(tsrc[i] + (size_t)c1 * tstep);
+    }
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) *(uint4*)&xs[tdst[i]] = tregA[i];
     __syncthreads();
 
-    for (int chunk = 0; chunk < nchunks; ++chunk) {
-        const bool more = chunk + 1 < nchunks;
-        if (more) {
-            load_tokens(chunk + 1);
-            load_weights(chunk + 1, wnext);
+    // nchunks is a multiple of PD+1 (the launcher picks PD so; PD is 0, 1 or 3),
+    // and every ring index below is a compile-time constant.
+    auto slice = [&](auto uc, int c0) {
+        constexpr int u = decltype(uc)::value;            // position in the ring: compile-time
+        const int c = c0 + u;
+        const int cw = min(c + PD, nchunks - 1), ct = min(c + TD, nchunks - 1);
+        const uint16_t* tile = xs + (c & 1) * stage_elems + xoff;
+        bf16x8 xf[2][NBF];
+#pragma unroll
+        for (int b = 0; b < NBF; ++b) xf[0][b] = as_frag(*(const uint4*)&tile[b * XB]);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int a = 0; a < AF; ++a)
+                wbuf[(u + PD) % (PD + 1)][ks][a] = wbase[a][(size_t)(cw * KS + ks) * 64];
+        // set u%TD held slice c (already in LDS); it now receives slice c+TD
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+            uint4 v = *(const uint4*)(tsrc[i] + (size_t)ct * tstep);
+            if constexpr (u % TD == 0) tregA[i] = v; else tregB[i] = v;
         }
-        const uint16_t* tile = xs[chunk & 1];
+        __builtin_amdgcn_sched_barrier(0);                // keep the prefetches ahead of the math
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
+            if (ks + 1 < KS) {
 #pragma unroll
-            for (int b = 0; b < BFR; ++b) {
-                if (b < nbf) {
-                    const int r = b * 32 + (lane & 31);
-                    bf16x8 xf = as_frag(*(const uint4*)&tile[r * LDR + ks * 16 + (lane >> 5) * 8]);
-#pragma unroll
-                    for (int a = 0; a < AF; ++a)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(wcur[ks][a]), xf,
-                                                                            acc[a][b], 0, 0, 0);
-                }
+                for (int b = 0; b < NBF; ++b)
+                    xf[(ks + 1) & 1][b] = as_frag(*(const uint4*)&tile[b * XB + (ks + 1) * XK]);
             }
+            __builtin_amdgcn_sched_barrier(0);            // next step's operands are on their way
+#pragma unroll
+            for (int b = 0; b < NBF; ++b)
+#pragma unroll
+                for (int a = 0; a < AF; ++a)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(wbuf[u][ks][a]), xf[ks & 1][b],
+                                                                        acc[a][b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (more) store_tokens((chunk + 1) & 1);
+        // slice c+1 (register set (u+1)%TD) goes into the other LDS stage
+        uint16_t* dst = xs + ((c + 1) & 1) * stage_elems;
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+            if constexpr ((u + 1) % TD == 0) *(uint4*)&dst[tdst[i]] = tregA[i];
+            else *(uint4*)&dst[tdst[i]] = tregB[i];
+        }
         __syncthreads();
-        if (more) {
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int a = 0; a < AF; ++a) wcur[ks][a] = wnext[ks][a];
+    };
+    for (int c0 = 0; c0 < nchunks; c0 += PD + 1) {
+        slice(std::integral_constant<int, 0>{}, c0);
+        if constexpr (PD >= 1) slice(std::integral_constant<int, 1>{}, c0);
+        if constexpr (PD >= 3) {
+            slice(std::integral_constant<int, 2>{}, c0);
+            slice(std::integral_constant<int, 3>{}, c0);
         }
     }
 
@@ -158,11 +242,16 @@ __global__ __launch_bounds__(NW * 64) void grouped_gemm_bf16(
     for (int a = 0; a < AF; ++a) {
         if (fb0 + a >= nfb) continue;
 #pragma unroll
-        for (int b = 0; b < BFR; ++b) {
-            if (b >= nbf) continue;
-            const int row = m0 + b * 32 + (lane & 31);
-            if (row >= m_end) continue;
-            uint16_t* yrow = Y + (size_t)row * N + (fb0 + a) * 32 + (lane >> 5) * 4;
+        for (int b = 0; b < NBF; ++b) {
+            uint16_t* ydst;
+            if (YFRAG) {   // unit [(pm0/32 + b)][(fb0+a)*4 + g][lane%32], 8 bytes at half (lane/32)
+                ydst = Y + (((size_t)((pm0 >> 5) + b) * (N >> 3) + (fb0 + a) * 4) * 32 + (lane & 31)) * 8 +
+                       (lane >> 5) * 4;
+            } else {
+                const int row = m0 + b * 32 + (lane & 31);
+                if (row >= m_end) continue;
+                ydst = Y + (size_t)row * N + (fb0 + a) * 32 + (lane >> 5) * 4;
+            }
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 float v0 = acc[a][b][4 * g], v1 = acc[a][b][4 * g + 1], v2 = acc[a][b][4 * g + 2],
@@ -171,33 +260,78 @@ __global__ __launch_bounds__(NW * 64) void grouped_gemm_bf16(
                 uint2 o;
                 o.x = (uint32_t)smoe_f32_to_bf16(v0) | ((uint32_t)smoe_f32_to_bf16(v1) << 16);
                 o.y = (uint32_t)smoe_f32_to_bf16(v2) | ((uint32_t)smoe_f32_to_bf16(v3) << 16);
-                *(uint2*)(yrow + 8 * g) = o;
+                *(uint2*)(ydst + (YFRAG ? g * 32 * 8 : g * 8)) = o;
             }
         }
     }
 }
 
-template <int AF, int BFR, int NW, bool RELU>
-void launch_gemm(const uint16_t* X, const void* Wp, const int32_t* offsets, int nslots, uint16_t* Y,
-                 int R, int N, int T, hipStream_t s) {
-    constexpr int BT = 32 * BFR;
-    int mtiles = (T + BT - 1) / BT + nslots;               // upper bound; surplus workgroups exit
-    int ftiles = ((N >> 5) + NW * AF - 1) / (NW * AF);
-    hipLaunchKernelGGL((grouped_gemm_bf16<AF, BFR, NW, RELU>), dim3(mtiles, ftiles), dim3(NW * 64), 0, s, X,
-                       (const uint4*)Wp, offsets, nslots, T, Y, R, N);
+template <int AF, int NBF, int MAXB, int NW, int BKT, int PD, bool XFRAG, bool YFRAG, bool RELU>
+struct TileSwitch {
+    static __device__ __forceinline__ void go(int nbf, const uint16_t* X, const uint4* Wp, uint16_t* Y, int R,
+                                              int N, int slot, int m0, int m_end, int pm0, int ftile,
+                                              uint16_t* xs) {
+        constexpr int stage = MAXB * 32 * (BKT + KPAD);
+        if (nbf == NBF)
+            run_tile<AF, NBF, NW, BKT, PD, XFRAG, YFRAG, RELU>(X, Wp, Y, R, N, slot, m0, m_end, pm0, ftile, xs,
+                                                               stage);
+        else if constexpr (NBF > 1)
+            TileSwitch<AF, NBF - 1, MAXB, NW, BKT, PD, XFRAG, YFRAG, RELU>::go(nbf, X, Wp, Y, R, N, slot, m0,
+                                                                              m_end, pm0, ftile, xs);
+    }
+};
+
+// FIRST = the d_model -> d_ff product: row-major x_perm in, ReLU, fragment-order h out.
+// Otherwise the d_ff -> d_model product: fragment-order h in, row-major y_perm out.
+template <int AF, int MAXB, int NW, int BKT, int PD, int OCC, bool FIRST>
+__global__ __launch_bounds__(NW * 64, OCC) void grouped_gemm_bf16(
+    const uint16_t* __restrict__ X, const uint4* __restrict__ Wp, const int32_t* __restrict__ offsets,
+    int nslots, int T, uint16_t* __restrict__ Y, int R, int N) {
+    __shared__ __align__(16) uint16_t xs[2 * MAXB * 32 * (BKT + KPAD)];
+    int slot, ftile, m0, m_end, pm0;
+    const int ftiles = ((N >> 5) + NW * AF - 1) / (NW * AF);
+    if (!find_item(offsets, nslots, T, MAXB * 32, ftiles, blockIdx.x, slot, ftile, m0, m_end, pm0)) return;
+    const int nbf = min(MAXB, (m_end - m0 + 31) >> 5);    // token blocks that hold real rows
+    TileSwitch<AF, MAXB, MAXB, NW, BKT, PD, !FIRST, FIRST, FIRST>::go(nbf, X, Wp, Y, R, N, slot, m0, m_end, pm0,
+                                                                     ftile, xs);
 }
 
-template <bool RELU>
+template <int AF, int MAXB, int NW, int BKT, int PD, int OCC, bool FIRST>
+void launch_gemm(const uint16_t* X, const void* Wp, const int32_t* offsets, int nslots, uint16_t* Y,
+                 int R, int N, int T, hipStream_t s) {
+    constexpr int BT = 32 * MAXB;
+    int mtiles = (T + BT - 1) / BT + nslots;               // upper bound on the row tiles of all slots
+    int ftiles = ((N >> 5) + NW * AF - 1) / (NW * AF);
+    // a die gets at most ceil(mtiles / 8) row tiles, each with all feature tiles; surplus workgroups exit
+    dim3 grid(XCDS * ((mtiles + XCDS - 1) / XCDS) * ftiles);
+    if ((R / BKT) % (PD + 1) == 0)
+        hipLaunchKernelGGL((grouped_gemm_bf16<AF, MAXB, NW, BKT, PD, OCC, FIRST>), grid, dim3(NW * 64), 0, s, X,
+                           (const uint4*)Wp, offsets, nslots, T, Y, R, N);
+    else   // slice count not a multiple of the ring length: same tile without weight prefetch
+        hipLaunchKernelGGL((grouped_gemm_bf16<AF, MAXB, NW, BKT, 0, OCC, FIRST>), grid, dim3(NW * 64), 0, s, X,
+                           (const uint4*)Wp, offsets, nslots, T, Y, R, N);
+}
+
+constexpr int N_VARIANTS = 10;
+
+template <bool FIRST>
 void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* offsets, int nslots,
                     uint16_t* Y, int R, int N, int T, hipStream_t s) {
-    switch (v) {
-        case 0: launch_gemm<2, 8, 4, RELU>(X, Wp, offsets, nslots, Y, R, N, T, s); break;  // 256 tok x 256 feat
-        case 1: launch_gemm<2, 4, 4, RELU>(X, Wp, offsets, nslots, Y, R, N, T, s); break;  // 128 x 256
-        case 2: launch_gemm<1, 8, 4, RELU>(X, Wp, offsets, nslots, Y, R, N, T, s); break;  // 256 x 128
-        case 3: launch_gemm<1, 4, 4, RELU>(X, Wp, offsets, nslots, Y, R, N, T, s); break;  // 128 x 128
-        case 4: launch_gemm<2, 2, 4, RELU>(X, Wp, offsets, nslots, Y, R, N, T, s); break;  //  64 x 256
-        case 5: launch_gemm<1, 2, 4, RELU>(X, Wp, offsets, nslots, Y, R, N, T, s); break;  //  64 x 128
-        default: launch_gemm<1, 1, 4, RELU>(X, Wp, offsets, nslots, Y, R, N, T, s); break; //  32 x 128
+    if (R % 64 != 0) {       // d_model / d_ff are multiples of 32 by contract: 32-deep slices always fit
+        launch_gemm<1, 4, 4, 32, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s);
+        return;
+    }
+    switch (v) {             //            AF MAXB NW BKT PD OCC     tokens x features per workgroup
+        case 0: launch_gemm<2, 8, 4, 64, 1, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   // 256 x 256
+        case 1: launch_gemm<2, 4, 4, 64, 3, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   // 128 x 256
+        case 2: launch_gemm<1, 8, 4, 64, 3, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   // 256 x 128
+        case 3: launch_gemm<1, 4, 4, 64, 3, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   // 128 x 128
+        case 4: launch_gemm<1, 4, 4, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   // 128 x 128
+        case 5: launch_gemm<2, 2, 4, 64, 3, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   //  64 x 256
+        case 6: launch_gemm<2, 2, 4, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   //  64 x 256
+        case 7: launch_gemm<1, 2, 4, 64, 3, 3, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   //  64 x 128
+        case 8: launch_gemm<1, 2, 4, 64, 1, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   //  64 x 128
+        default: launch_gemm<1, 1, 4, 64, 3, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;  //  32 x 128
     }
 }
 
@@ -205,14 +339,16 @@ void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* off
 // built-in choice (a tuning aid; the indices are those of launch_variant).
 void pick_variants(const smoe_config& c, int T, int& v1, int& v2) {
     int per_slot = T / c.K;
-    if (per_slot >= 192) { v1 = 0; v2 = 1; }
-    else if (per_slot >= 96) { v1 = 1; v2 = 3; }
-    else if (per_slot >= 48) { v1 = 4; v2 = 5; }
-    else { v1 = 6; v2 = 6; }
-    static const char* env = getenv("SMOE_FFN_VARIANT");
+    if (per_slot >= 96) { v1 = 3; v2 = 3; }
+    else if (per_slot >= 48) { v1 = 5; v2 = 7; }
+    else { v1 = 9; v2 = 9; }
+    const char* env = getenv("SMOE_FFN_VARIANT");
     if (env) {
         int a = -1, b = -1;
-        if (sscanf(env, "%d,%d", &a, &b) == 2 && a >= 0 && b >= 0) { v1 = a; v2 = b; }
+        if (sscanf(env, "%d,%d", &a, &b) == 2 && a >= 0 && b >= 0 && a < N_VARIANTS && b < N_VARIANTS) {
+            v1 = a;
+            v2 = b;
+        }
     }
 }
 
