@@ -87,7 +87,9 @@ size_t smoe_workspace_bytes(const smoe_layer_t* layer);
 size_t smoe_slot_weight_bytes(const smoe_layer_t* layer);
 
 /* Binds the caller-owned device buffers the layer works on.
- *   router_w    [E, d_model] fp32, the router G's weight (no bias)
+ *   router_w    [E, d_model] fp32, the router G's weight (no bias); the first
+ *               smoe_route after a bind may keep a re-formatted copy in the
+ *               workspace, so re-bind after changing the router's weights
  *   slot_w1/2   smoe_slot_weight_bytes() each, 256-byte aligned, contents
  *               written only by smoe_set_resident
  *   expert_norm [E] fp32, |E_i| of Eq. 1 for every expert of the bank

@@ -43,6 +43,9 @@ smoe_ws_layout smoe_ws_plan(const smoe_config& c) {
     // hidden activations: every segment is re-based to a multiple of 32 rows
     w.hidden = off;  off = align_up(off + ((size_t)c.max_tokens + 32 * (size_t)c.K) * c.d_ff * smoe_elem_size(c.dtype), 256);
     w.partial = off; off = align_up(off, 256);
+    // bf16 path: three bf16 pieces of every router weight, experts padded to a multiple of 32
+    w.rsplit = off;
+    if (c.dtype == SMOE_BF16) off = align_up(off + (size_t)((c.E + 31) / 32 * 32) * c.d_model * 2 * 3, 256);
     w.total = off;
     return w;
 }
@@ -115,6 +118,8 @@ int smoe_bind(smoe_layer_t* L, const float* router_w, void* slot_w1, void* slot_
     L->d_sort_hist = (int32_t*)(L->workspace + w.hist);
     L->d_hidden = L->workspace + w.hidden;
     L->d_partial = (float*)(L->workspace + w.partial);
+    L->d_router_split = L->workspace + w.rsplit;
+    L->router_split_done = false;
     std::fill(L->slot_to_expert.begin(), L->slot_to_expert.end(), -1);
     std::fill(L->expert_to_slot.begin(), L->expert_to_slot.end(), -1);
     L->slots_set = 0;
@@ -216,6 +221,11 @@ int smoe_route(smoe_layer_t* L, const void* x, int T, int32_t* orig_expert, floa
     if (!x || !orig_expert || !orig_gate || !slot || !gate || !xnorm)
         return smoe_fail(SMOE_EINVAL, "smoe_route: null buffer");
     if (misaligned(x, 16)) return smoe_fail(SMOE_EINVAL, "smoe_route: x must be 16-byte aligned");
+    if (L->cfg.dtype == SMOE_BF16 && !L->router_split_done) {
+        rc = smoe_launch_split_router(L, as_stream(stream));
+        if (rc) return rc;
+        L->router_split_done = true;
+    }
     return smoe_launch_route(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, as_stream(stream));
 }
 

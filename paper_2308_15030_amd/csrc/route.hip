@@ -157,6 +157,202 @@ __global__ __launch_bounds__(THREADS) void route_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------
+// bf16 activations: the router product on the matrix cores at fp32 accuracy.
+//
+// x is exactly bf16, and an fp32 router weight is exactly the sum of three
+// bf16 numbers (8 + 8 + 8 significand bits): w = hi + mid + lo.  Every product
+// x * {hi, mid, lo} is exact in fp32, so three bf16 MFMA passes with fp32
+// accumulation give the fp32-weight logits up to accumulation rounding -- the
+// same error class as an fp32 FMA chain, at matrix-core speed.  The split
+// weights are kept in MFMA operand order in the workspace (made on the first
+// smoe_route after smoe_bind).
+//
+// One workgroup = 32 tokens x all experts.  Its 4 waves split the reduction
+// (d_model) four ways, each accumulating a partial [experts x 32 tokens] tile;
+// the partials meet in LDS and are added in wave order (fixed, so results are
+// reproducible), then the same 8-lanes-per-token epilogue as above runs.
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ bf16x8 frag_of(uint4 v) {
+    union { uint4 u; bf16x8 b; } c;
+    c.u = v;
+    return c.b;
+}
+
+// Wr [E, d] fp32 -> units [eb][kb][split][lane] of 8 bf16: expert eb*32 + lane%32,
+// reduction index kb*16 + (lane/32)*8 + i.  Experts past E are zero.
+__global__ __launch_bounds__(256) void split_router_kernel(const float* __restrict__ Wr, int E, int d,
+                                                           uint4* __restrict__ out, int neb) {
+    int unit = blockIdx.x * 256 + threadIdx.x;             // (eb * nkb + kb) * 64 + lane
+    int nkb = d >> 4;
+    if (unit >= neb * nkb * 64) return;
+    int lane = unit & 63, kb = (unit >> 6) % nkb, eb = (unit >> 6) / nkb;
+    int e = eb * 32 + (lane & 31), k0 = kb * 16 + (lane >> 5) * 8;
+    uint32_t hi[8], mid[8], lo[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float w = e < E ? Wr[(size_t)e * d + k0 + i] : 0.f;
+        uint16_t h = smoe_f32_to_bf16(w);
+        float r1 = w - smoe_bf16_to_f32(h);                // exact
+        uint16_t m = smoe_f32_to_bf16(r1);
+        float r2 = r1 - smoe_bf16_to_f32(m);               // exact
+        hi[i] = h; mid[i] = m; lo[i] = smoe_f32_to_bf16(r2);
+    }
+    uint4* dst = out + ((size_t)(eb * nkb + kb) * 3) * 64 + lane;
+    dst[0] = make_uint4(hi[0] | hi[1] << 16, hi[2] | hi[3] << 16, hi[4] | hi[5] << 16, hi[6] | hi[7] << 16);
+    dst[64] = make_uint4(mid[0] | mid[1] << 16, mid[2] | mid[3] << 16, mid[4] | mid[5] << 16, mid[6] | mid[7] << 16);
+    dst[128] = make_uint4(lo[0] | lo[1] << 16, lo[2] | lo[3] << 16, lo[4] | lo[5] << 16, lo[6] | lo[7] << 16);
+}
+
+constexpr int RT = 32;            // tokens per workgroup
+constexpr int RTP = RT + 1;       // padded row of the partial-logit tile
+
+// NEB = 32-expert blocks, NWR = waves per workgroup (each takes 1/NWR of d_model).
+template <int NEB, int NWR>
+__global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
+    const uint16_t* __restrict__ x, const uint4* __restrict__ Wsplit, const int32_t* __restrict__ e2s,
+    int T, int d, int E, int gate_mode,
+    int32_t* __restrict__ orig_expert, float* __restrict__ orig_gate, int32_t* __restrict__ slot,
+    float* __restrict__ gate, float* __restrict__ xnorm) {
+    extern __shared__ __align__(16) float smem[];
+    constexpr int EP = NEB * 32;
+    constexpr int THREADS = NWR * 64;
+    // reduction steps whose operands are fetched together, so that one memory
+    // round trip feeds several MFMAs: bounded by registers (1 + 3*NEB loads per step)
+    constexpr int G = NEB == 1 ? 8 : NEB == 2 ? 4 : NEB <= 5 ? 2 : 1;
+    float* part = smem;                           // [NWR waves][EP][RTP] partial logits
+    float* sqp = smem + NWR * EP * RTP;           // [NWR waves][2 halves][RT] partial sums of squares
+    __shared__ int32_t s_e2s[EP];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int t0 = blockIdx.x * RT;
+    for (int e = tid; e < EP; e += THREADS) s_e2s[e] = e < E ? e2s[e] : -1;
+
+    const int nkb = d >> 4;
+    const int per = (nkb + NWR - 1) / NWR;
+    const int kb_lo = min(wave * per, nkb), kb_hi = min(kb_lo + per, nkb);
+    const int trow = min(t0 + (lane & 31), T - 1);
+    const uint16_t* xp = x + (size_t)trow * d + (lane >> 5) * 8;
+    const uint4* wp = Wsplit + lane;
+
+    f32x16 acc[NEB];
+#pragma unroll
+    for (int b = 0; b < NEB; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
+    float sq = 0.f;
+
+    for (int g0 = kb_lo; g0 < kb_hi; g0 += G) {
+        uint4 xv[G];
+        uint4 w[G][NEB][3];
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            const int kb = min(g0 + i, kb_hi - 1);            // past the end: reloaded, not used
+            xv[i] = *(const uint4*)(xp + kb * 16);
+#pragma unroll
+            for (int b = 0; b < NEB; ++b)
+#pragma unroll
+                for (int s3 = 0; s3 < 3; ++s3) w[i][b][s3] = wp[((size_t)(b * nkb + kb) * 3 + s3) * 64];
+        }
+        __builtin_amdgcn_sched_barrier(0);                    // all of the group's loads are issued first
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            if (g0 + i < kb_hi) {
+                uint32_t xw[4] = {xv[i].x, xv[i].y, xv[i].z, xv[i].w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float a = __uint_as_float(xw[q] << 16), c = __uint_as_float(xw[q] & 0xFFFF0000u);
+                    sq = fmaf(a, a, sq);
+                    sq = fmaf(c, c, sq);
+                }
+                bf16x8 xf = frag_of(xv[i]);
+                // smallest terms first, so they are not absorbed by the large partial sums
+#pragma unroll
+                for (int s3 = 2; s3 >= 0; --s3)
+#pragma unroll
+                    for (int b = 0; b < NEB; ++b)
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_of(w[i][b][s3]), xf, acc[b], 0, 0, 0);
+            }
+        }
+    }
+    // accumulator register i of lane l: expert 8*(i/4) + 4*(l/32) + i%4 (+32 per block), token l%32
+#pragma unroll
+    for (int b = 0; b < NEB; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            int e = b * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+            part[(wave * EP + e) * RTP + (lane & 31)] = acc[b][i];
+        }
+    sqp[(wave * 2 + (lane >> 5)) * RT + (lane & 31)] = sq;
+    __syncthreads();
+
+    // epilogue: the first 256 threads, lanes 8*st .. 8*st+7 own token st
+    if (tid >= 256) return;
+    const int st = tid >> 3, sub = tid & 7;
+    const int tok = t0 + st;
+    float best = -INFINITY, rbest = -INFINITY;
+    int bi = 0x7fffffff, rbi = 0x7fffffff;
+    for (int e = sub; e < E; e += 8) {
+        float v = part[e * RTP + st];
+#pragma unroll
+        for (int w = 1; w < NWR; ++w) v += part[(w * EP + e) * RTP + st];     // fixed order
+        part[e * RTP + st] = v;                   // wave 0's slot now holds the full logit
+        if (v > best) { best = v; bi = e; }
+        if (s_e2s[e] >= 0 && v > rbest) { rbest = v; rbi = e; }
+    }
+#pragma unroll
+    for (int m = 1; m < 8; m <<= 1) {
+        float ov = __shfl_xor(best, m); int oi = __shfl_xor(bi, m);
+        if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+        float rv = __shfl_xor(rbest, m); int ri = __shfl_xor(rbi, m);
+        if (rv > rbest || (rv == rbest && ri < rbi)) { rbest = rv; rbi = ri; }
+    }
+    float z = 0.f, zr = 0.f;
+    for (int e = sub; e < E; e += 8) {
+        float p = expf(part[e * RTP + st] - best);
+        z += p;
+        if (s_e2s[e] >= 0) zr += p;
+    }
+#pragma unroll
+    for (int m = 1; m < 8; m <<= 1) {
+        z += __shfl_xor(z, m);
+        zr += __shfl_xor(zr, m);
+    }
+    if (sub == 0 && tok < T) {
+        float ss = 0.f;
+#pragma unroll
+        for (int q = 0; q < 2 * NWR; ++q) ss += sqp[q * RT + st];
+        float ps = expf(rbest - best);
+        orig_expert[tok] = bi;
+        orig_gate[tok] = 1.0f / z;
+        slot[tok] = rbi < EP ? s_e2s[rbi] : 0;    // rbi is always valid once every slot is set
+        gate[tok] = gate_mode == SMOE_GATE_RENORM ? ps / zr : ps / z;
+        xnorm[tok] = sqrtf(ss);
+    }
+}
+
+template <int NEB>
+int launch_mfma(const smoe_layer* L, const void* x, int T, int32_t* oe, float* og, int32_t* sl, float* g,
+                float* xn, hipStream_t s) {
+    constexpr int EP = NEB * 32;
+    constexpr int NWR = NEB <= 2 ? 8 : 4;
+    size_t lds = (size_t)(NWR * EP * RTP + 2 * NWR * RT) * 4;
+    auto kern = route_mfma_kernel<NEB, NWR>;
+    if (lds > 48 * 1024) {
+        int rc = smoe_check_hip(hipFuncSetAttribute((const void*)kern,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
+                                "smoe_route: LDS size");
+        if (rc) return rc;
+    }
+    hipLaunchKernelGGL(kern, dim3((T + RT - 1) / RT), dim3(NWR * 64), lds, s, (const uint16_t*)x,
+                       (const uint4*)L->d_router_split, L->d_expert_to_slot, T, L->cfg.d_model, L->cfg.E,
+                       L->cfg.gate_mode, oe, og, sl, g, xn);
+    return smoe_check_hip(hipGetLastError(), "smoe_route launch");
+}
+
 template <typename XT, int NEC>
 int launch(const smoe_layer* L, const void* x, int T, int32_t* oe, float* og, int32_t* sl, float* g,
            float* xn, hipStream_t s) {
@@ -192,9 +388,27 @@ int dispatch(const smoe_layer* L, const void* x, int T, int32_t* oe, float* og, 
 
 }  // namespace
 
+int smoe_launch_split_router(const smoe_layer* L, hipStream_t s) {
+    const int neb = (L->cfg.E + 31) / 32;
+    const int units = neb * (L->cfg.d_model >> 4) * 64;
+    hipLaunchKernelGGL(split_router_kernel, dim3((units + 255) / 256), dim3(256), 0, s, L->router_w, L->cfg.E,
+                       L->cfg.d_model, (uint4*)L->d_router_split, neb);
+    return smoe_check_hip(hipGetLastError(), "smoe_route: router split launch");
+}
+
 int smoe_launch_route(const smoe_layer* L, const void* x, int T, int32_t* orig_expert,
                       float* orig_gate, int32_t* slot, float* gate, float* xnorm, hipStream_t s) {
     if (L->cfg.dtype == SMOE_F32)
         return dispatch<float>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, s);
-    return dispatch<uint16_t>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, s);
+    switch ((L->cfg.E + 31) / 32) {
+        case 1: return launch_mfma<1>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, s);
+        case 2: return launch_mfma<2>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, s);
+        case 3: return launch_mfma<3>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, s);
+        case 4: return launch_mfma<4>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, s);
+        case 5: return launch_mfma<5>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, s);
+        case 6: return launch_mfma<6>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, s);
+        case 7: return launch_mfma<7>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, s);
+        case 8: return launch_mfma<8>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, s);
+        default: return smoe_fail(SMOE_EINVAL, "smoe_route: E=%d exceeds 256", L->cfg.E);
+    }
 }

@@ -33,12 +33,14 @@ struct smoe_layer {
     int32_t* d_sort_hist = nullptr;          // [sort blocks, K]
     void* d_hidden = nullptr;                // [max_tokens, d_ff] activations of the FFN
     float* d_partial = nullptr;              // small-T FFN: split partial sums
+    void* d_router_split = nullptr;          // bf16 path: router weights split in three, MFMA order
+    bool router_split_done = false;          // made by the first smoe_route after a bind
 
     hipEvent_t prof_ev[3] = {nullptr, nullptr, nullptr};   // one-shot FFN profiling events
 };
 
 struct smoe_ws_layout {
-    size_t e2s, s2e, hist, hidden, partial, total;
+    size_t e2s, s2e, hist, hidden, partial, rsplit, total;
 };
 smoe_ws_layout smoe_ws_plan(const smoe_config& c);
 
@@ -68,6 +70,7 @@ int smoe_launch_load_slot(const smoe_layer* L, int slot, int expert, int old_exp
 int smoe_launch_expert_norm(const smoe_layer* L, const void* w1, const void* w2, int n, float* out,
                             hipStream_t s);
 int smoe_launch_clear_maps(const smoe_layer* L, hipStream_t s);
+int smoe_launch_split_router(const smoe_layer* L, hipStream_t s);
 
 // bf16 <-> fp32 on the device.  Widening is exact; narrowing rounds to
 // nearest, ties to even (inputs are finite by contract).
