@@ -99,7 +99,8 @@ size_t smoe_slot_weight_bytes(const smoe_layer_t* layer);
 int smoe_bind(smoe_layer_t* layer, const float* router_w, void* slot_w1, void* slot_w2,
               const float* expert_norm, void* workspace);
 
-/* |E_i| of Eq. 1 for n experts stored in bank layout: w1 [n, d_model, d_ff],
+/* |E_i| of Eq. 1 for n <= E experts stored in bank layout (the layer must be
+ * bound: partial sums use its workspace): w1 [n, d_model, d_ff],
  * w2 [n, d_ff, d_model] in the layer's dtype -> out [n] fp32, the Frobenius
  * norm of all of the expert's parameters, sqrt(|W1_i|^2 + |W2_i|^2).  The same
  * magnitude ranks experts in the paper's "Pruning" baseline (Section 4.1). */

@@ -46,6 +46,9 @@ smoe_ws_layout smoe_ws_plan(const smoe_config& c) {
     // bf16 path: three bf16 pieces of every router weight, experts padded to a multiple of 32
     w.rsplit = off;
     if (c.dtype == SMOE_BF16) off = align_up(off + (size_t)((c.E + 31) / 32 * 32) * c.d_model * 2 * 3, 256);
+    w.imp = off;     off = align_up(off + (size_t)((c.max_tokens + 255) / 256) * 3 * c.E * 4, 256);
+    w.ticket = off;  off = align_up(off + 256, 256);
+    w.norm = off;    off = align_up(off + (size_t)c.E * 64 * 4, 256);      // smoe_expert_norm partial sums
     w.total = off;
     return w;
 }
@@ -120,6 +123,10 @@ int smoe_bind(smoe_layer_t* L, const float* router_w, void* slot_w1, void* slot_
     L->d_partial = (float*)(L->workspace + w.partial);
     L->d_router_split = L->workspace + w.rsplit;
     L->router_split_done = false;
+    L->d_imp_partial = (float*)(L->workspace + w.imp);
+    L->d_imp_ticket = (int32_t*)(L->workspace + w.ticket);
+    L->ws_ready = false;
+    L->d_norm_partial = (float*)(L->workspace + w.norm);
     std::fill(L->slot_to_expert.begin(), L->slot_to_expert.end(), -1);
     std::fill(L->expert_to_slot.begin(), L->expert_to_slot.end(), -1);
     L->slots_set = 0;
@@ -136,12 +143,22 @@ int smoe_get_maps(const smoe_layer_t* L, int32_t* slot_to_expert, int32_t* exper
 
 int smoe_expert_norm(smoe_layer_t* L, const void* w1, const void* w2, int n, float* out, void* stream) {
     if (!L) return smoe_fail(SMOE_EINVAL, "smoe_expert_norm: null handle");
-    if (n < 0) return smoe_fail(SMOE_EINVAL, "smoe_expert_norm: n=%d < 0", n);
+    if (n < 0 || n > L->cfg.E) return smoe_fail(SMOE_EINVAL, "smoe_expert_norm: n=%d outside [0,E]", n);
     if (n == 0) return SMOE_OK;
     if (!w1 || !w2 || !out) return smoe_fail(SMOE_EINVAL, "smoe_expert_norm: null buffer");
     if (misaligned(w1, 16) || misaligned(w2, 16))
         return smoe_fail(SMOE_EINVAL, "smoe_expert_norm: weights must be 16-byte aligned");
     return smoe_launch_expert_norm(L, w1, w2, n, out, as_stream(stream));
+}
+
+// First stream work after a bind: the device maps and counters in the workspace
+// are uninitialised memory until this has run.
+static int ensure_workspace(smoe_layer* L, hipStream_t s) {
+    if (L->ws_ready) return SMOE_OK;
+    int rc = smoe_launch_clear_maps(L, s);
+    if (rc) return rc;
+    L->ws_ready = true;
+    return SMOE_OK;
 }
 
 int smoe_set_resident(smoe_layer_t* L, int slot, int expert, const void* w1_src, const void* w2_src,
@@ -159,11 +176,8 @@ int smoe_set_resident(smoe_layer_t* L, int slot, int expert, const void* w1_src,
     if (cur >= 0 && cur != slot)
         return smoe_fail(SMOE_ESTATE, "smoe_set_resident: expert %d is already resident in slot %d", expert, cur);
     hipStream_t s = as_stream(stream);
-    if (L->slots_set == 0) {
-        // first load after a bind: the device maps are uninitialised memory
-        int rc = smoe_launch_clear_maps(L, s);
-        if (rc) return rc;
-    }
+    int rc0 = ensure_workspace(L, s);
+    if (rc0) return rc0;
     int old = L->slot_to_expert[slot];
     int rc = smoe_launch_load_slot(L, slot, expert, old, w1_src, w2_src, s);
     if (rc) return rc;
@@ -240,6 +254,8 @@ int smoe_importance(smoe_layer_t* L, const int32_t* orig_expert, const float* or
     if (T > 0 && (!orig_expert || !orig_gate || !xnorm))
         return smoe_fail(SMOE_EINVAL, "smoe_importance: null input");
     if (T == 0 && accumulate == 1) return SMOE_OK;
+    rc = ensure_workspace(L, as_stream(stream));
+    if (rc) return rc;
     return smoe_launch_importance(L, orig_expert, orig_gate, xnorm, T, count, gsum, score, accumulate,
                                   as_stream(stream));
 }

@@ -53,36 +53,65 @@ constexpr int XCDS = 8;   // MI355X: 8 accelerator dies, each with a private L2
 // Returns false when the die has fewer items than wg / 8.
 // Outputs: slot, feature tile, first row m0, segment end m_end, and pm0 = the
 // padded row (segments re-based to multiples of 32) that m0 maps to.
+__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        int o = __shfl_up(v, d);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+// Every wave works the answer out on its own, slot k on lane k % 64 (64 slots
+// per pass): one vector load of the offsets, two wave scans, one ballot -- no
+// chain of dependent scalar loads at the head of every workgroup.
 __device__ __forceinline__ bool find_item(const int32_t* __restrict__ offsets, int nslots, int T, int bt,
                                           int ftiles, int wg, int& slot, int& ftile, int& m0, int& m_end,
                                           int& pm0) {
+    const int lane = threadIdx.x & 63;
+    // pass 1: number of row tiles over all slots
     int total = 0;
-    {
-        int a = min(max(offsets[0], 0), T);                 // clamps guard misuse
-        for (int k = 0; k < nslots; ++k) {
-            int b = min(max(offsets[k + 1], a), T);
-            total += (b - a + bt - 1) / bt;
-            a = b;
+    for (int base = 0; base < nslots; base += 64) {
+        const int k = base + lane;
+        int tiles = 0;
+        if (k < nslots) {
+            int a = min(max(offsets[k], 0), T), b = max(min(max(offsets[k + 1], 0), T), a);   // clamps guard misuse
+            tiles = (b - a + bt - 1) / bt;
         }
+        total += __shfl(wave_incl_scan(tiles, lane), 63);
     }
     const int die = wg % XCDS, j = wg / XCDS;
     const int lo = (int)((long long)total * die / XCDS), hi = (int)((long long)total * (die + 1) / XCDS);
     const int cnt = hi - lo;
     if (cnt <= 0 || j >= cnt * ftiles) return false;
     ftile = j / cnt;
-    int mt = lo + j % cnt;                                  // index into the global row-tile list
-    int pbase = 0;
-    int a = min(max(offsets[0], 0), T);
-    for (int k = 0; k < nslots; ++k) {
-        int b = min(max(offsets[k + 1], a), T);
-        int tiles = (b - a + bt - 1) / bt;
-        if (mt < tiles) {
-            slot = k; m0 = a + mt * bt; m_end = b; pm0 = pbase + mt * bt;
+    const int mt = lo + j % cnt;                            // index into the global row-tile list
+    // pass 2: the slot that holds row tile mt, and the padded rows before it
+    int tiles_before = 0, pad_before = 0;
+    for (int base = 0; base < nslots; base += 64) {
+        const int k = base + lane;
+        int a = 0, b = 0, tiles = 0, pad = 0;
+        if (k < nslots) {
+            a = min(max(offsets[k], 0), T);
+            b = max(min(max(offsets[k + 1], 0), T), a);
+            tiles = (b - a + bt - 1) / bt;
+            pad = (b - a + 31) & ~31;
+        }
+        const int tin = wave_incl_scan(tiles, lane), pin = wave_incl_scan(pad, lane);
+        const int first = tiles_before + tin - tiles;       // first row tile of this lane's slot
+        const unsigned long long hit = __ballot(tiles > 0 && mt >= first && mt < first + tiles);
+        if (hit) {
+            const int src = __ffsll((long long)hit) - 1;
+            const int sa = __shfl(a, src), sb = __shfl(b, src);
+            const int sfirst = __shfl(first, src), spad = __shfl(pad_before + pin - pad, src);
+            slot = base + src;
+            m0 = sa + (mt - sfirst) * bt;
+            m_end = sb;
+            pm0 = spad + (mt - sfirst) * bt;
             return true;
         }
-        mt -= tiles;
-        pbase += (b - a + 31) & ~31;
-        a = b;
+        tiles_before += __shfl(tin, 63);
+        pad_before += __shfl(pin, 63);
     }
     return false;
 }
@@ -339,7 +368,7 @@ void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* off
 // built-in choice (a tuning aid; the indices are those of launch_variant).
 void pick_variants(const smoe_config& c, int T, int& v1, int& v2) {
     int per_slot = T / c.K;
-    if (per_slot >= 96) { v1 = 3; v2 = 3; }
+    if (per_slot >= 96) { v1 = 4; v2 = 4; }
     else if (per_slot >= 48) { v1 = 5; v2 = 7; }
     else { v1 = 9; v2 = 9; }
     const char* env = getenv("SMOE_FFN_VARIANT");

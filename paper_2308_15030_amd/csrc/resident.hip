@@ -15,10 +15,11 @@
 
 namespace {
 
-__global__ void clear_maps_kernel(int32_t* e2s, int E, int32_t* s2e, int K) {
+__global__ void clear_maps_kernel(int32_t* e2s, int E, int32_t* s2e, int K, int32_t* ticket) {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < E) e2s[i] = -1;
     if (i < K) s2e[i] = -1;
+    if (i == 0) *ticket = 0;
 }
 
 __global__ void set_map_kernel(int32_t* e2s, int32_t* s2e, int slot, int expert, int old_expert) {
@@ -108,7 +109,7 @@ __global__ void norm_finish_kernel(const float* __restrict__ partial, int n, flo
 int smoe_launch_clear_maps(const smoe_layer* L, hipStream_t s) {
     int n = L->cfg.E > L->cfg.K ? L->cfg.E : L->cfg.K;
     hipLaunchKernelGGL(clear_maps_kernel, dim3((n + 255) / 256), dim3(256), 0, s, L->d_expert_to_slot,
-                       L->cfg.E, L->d_slot_to_expert, L->cfg.K);
+                       L->cfg.E, L->d_slot_to_expert, L->cfg.K, L->d_imp_ticket);
     return smoe_check_hip(hipGetLastError(), "smoe_set_resident: map reset");
 }
 
@@ -140,14 +141,9 @@ int smoe_launch_load_slot(const smoe_layer* L, int slot, int expert, int old_exp
 
 int smoe_launch_expert_norm(const smoe_layer* L, const void* w1, const void* w2, int n, float* out,
                             hipStream_t s) {
-    // The partial sums live in the FFN's hidden-activation area of the workspace
-    // (n * 64 floats); the layer must be bound and n * 256 bytes must fit.
     if (!L->bound) return smoe_fail(SMOE_ESTATE, "smoe_expert_norm: call smoe_bind first");
     const smoe_config& c = L->cfg;
-    size_t avail = (size_t)c.max_tokens * c.d_ff * smoe_elem_size(c.dtype);
-    if ((size_t)n * NORM_CHUNKS * 4 > avail)
-        return smoe_fail(SMOE_EINVAL, "smoe_expert_norm: n=%d too large for the bound workspace", n);
-    float* partial = (float*)L->d_hidden;
+    float* partial = L->d_norm_partial;                       // [n <= E][NORM_CHUNKS]
     size_t n16 = (size_t)c.d_model * c.d_ff * smoe_elem_size(c.dtype) / 16;
     dim3 grid(NORM_CHUNKS, n);
     if (c.dtype == SMOE_BF16)

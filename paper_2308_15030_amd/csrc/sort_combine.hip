@@ -1,9 +1,9 @@
 // smoe_importance, smoe_permute and smoe_combine: the memory-bound steps
 // around the expert FFN.
 //
-//  * importance (SwapMoE Eq. 1): one workgroup per expert walks all T tokens
-//    and keeps those whose original choice is that expert; a fixed-shape LDS
-//    tree gives the three sums, so the result is bit-reproducible (no atomics).
+//  * importance (SwapMoE Eq. 1): per-block partial sums in token order, added
+//    up in block order by whichever block finishes last, so the result is
+//    bit-reproducible (no floating-point atomics).
 //  * permute: stable counting sort by slot in three launches -- per-block
 //    histograms, a ranking pass that turns them into exact positions with
 //    wavefront ballots (no atomics on positions, hence one unique, stable
@@ -16,36 +16,60 @@
 namespace {
 
 // ------------------------------------------------------------- importance
+// A block takes 256 consecutive tokens into LDS; thread e then walks them in
+// token order and keeps those whose original choice is expert e, which gives
+// per-block partial sums in a fixed order.  The block that finishes last (an
+// integer ticket) adds the partials block by block, again in a fixed order, so
+// the result does not depend on scheduling: no floating-point atomics.
 constexpr int IMP_THREADS = 256;
 
 __global__ __launch_bounds__(IMP_THREADS) void importance_kernel(
     const int32_t* __restrict__ orig_expert, const float* __restrict__ orig_gate,
-    const float* __restrict__ xnorm, const float* __restrict__ expert_norm, int T,
+    const float* __restrict__ xnorm, const float* __restrict__ expert_norm, int T, int E,
+    float* __restrict__ partial /* [blocks][3][E] */, int32_t* __restrict__ ticket,
     int32_t* __restrict__ count, float* __restrict__ gsum, float* __restrict__ score, int accumulate) {
-    __shared__ int32_t s_c[IMP_THREADS];
+    __shared__ int32_t s_e[IMP_THREADS];
     __shared__ float s_g[IMP_THREADS], s_r[IMP_THREADS];
-    const int e = blockIdx.x, tid = threadIdx.x;
-    int c = 0;
-    float g = 0.f, r = 0.f;
-    for (int t = tid; t < T; t += IMP_THREADS) {
-        if (orig_expert[t] == e) {
-            float gv = orig_gate[t];
-            c += 1;
-            g += gv;
-            r = fmaf(xnorm[t], gv, r);
-        }
-    }
-    s_c[tid] = c; s_g[tid] = g; s_r[tid] = r;
+    __shared__ int s_last;
+    const int tid = threadIdx.x, blk = blockIdx.x, nblk = gridDim.x;
+    const int t = blk * IMP_THREADS + tid;
+    s_e[tid] = t < T ? orig_expert[t] : -1;
+    const float gv = t < T ? orig_gate[t] : 0.f;
+    s_g[tid] = gv;
+    s_r[tid] = t < T ? xnorm[t] * gv : 0.f;
     __syncthreads();
-    for (int w = IMP_THREADS / 2; w > 0; w >>= 1) {
-        if (tid < w) { s_c[tid] += s_c[tid + w]; s_g[tid] += s_g[tid + w]; s_r[tid] += s_r[tid + w]; }
-        __syncthreads();
+    if (tid < E) {
+        int c = 0;
+        float g = 0.f, r = 0.f;
+        const int n = min(IMP_THREADS, T - blk * IMP_THREADS);
+        for (int i = 0; i < n; ++i) {
+            if (s_e[i] == tid) { c += 1; g += s_g[i]; r += s_r[i]; }
+        }
+        float* p = partial + (size_t)blk * 3 * E;
+        p[tid] = __int_as_float(c);
+        p[E + tid] = g;
+        p[2 * E + tid] = r;
     }
-    if (tid == 0) {
-        float sc = expert_norm[e] * s_r[0];
-        if (accumulate) { count[e] += s_c[0]; gsum[e] += s_g[0]; score[e] += sc; }
-        else { count[e] = s_c[0]; gsum[e] = s_g[0]; score[e] = sc; }
+    __threadfence();                                   // partials visible before the ticket is taken
+    __syncthreads();
+    if (tid == 0) s_last = atomicAdd(ticket, 1) == nblk - 1;
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    if (tid < E) {
+        int c = 0;
+        float g = 0.f, r = 0.f;
+        for (int b = 0; b < nblk; ++b) {
+            const float* p = partial + (size_t)b * 3 * E;
+            c += __float_as_int(__builtin_nontemporal_load(&p[tid]));
+            g += __builtin_nontemporal_load(&p[E + tid]);
+            r += __builtin_nontemporal_load(&p[2 * E + tid]);
+        }
+        const float sc = expert_norm[tid] * r;
+        if (accumulate) { count[tid] += c; gsum[tid] += g; score[tid] += sc; }
+        else { count[tid] = c; gsum[tid] = g; score[tid] = sc; }
     }
+    if (tid == 0) *ticket = 0;                         // ready for the next call
 }
 
 // ------------------------------------------------------------- permute
@@ -68,6 +92,8 @@ __global__ __launch_bounds__(SB) void sort_hist_kernel(const int32_t* __restrict
 
 // Position of token t = offsets[slot] + (tokens of that slot in earlier blocks)
 //                     + (in earlier waves of this block) + (in lower lanes of this wave).
+// With a single block (T <= 1024) the histogram pass is skipped (hist == nullptr)
+// and the block's own wave counts give the totals.
 __global__ __launch_bounds__(SB) void sort_rank_kernel(const int32_t* __restrict__ slot, int T, int K,
                                                        int nblk, const int32_t* __restrict__ hist,
                                                        int32_t* __restrict__ perm,
@@ -80,28 +106,8 @@ __global__ __launch_bounds__(SB) void sort_rank_kernel(const int32_t* __restrict
     const int tid = threadIdx.x, blk = blockIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
 
-    for (int k = tid; k < K; k += SB) {
-        int before = 0, total = 0;
-        for (int b = 0; b < nblk; ++b) {
-            int h = hist[(size_t)b * K + k];
-            if (b < blk) before += h;
-            total += h;
-        }
-        s_base[k] = before;
-        s_total[k] = total;
-    }
     for (int i = tid; i < SB_WAVES * K; i += SB) s_wave[i] = 0;
     __syncthreads();
-    if (tid == 0) {                          // exclusive scan over slots (K <= 256)
-        int run = 0;
-        for (int k = 0; k < K; ++k) {
-            int tot = s_total[k];
-            if (blk == 0) offsets[k] = run;
-            s_base[k] += run;
-            run += tot;
-        }
-        if (blk == 0) offsets[K] = run;
-    }
 
     const int t = blk * SB + tid;
     int my = t < T ? slot[t] : -1;
@@ -124,6 +130,28 @@ __global__ __launch_bounds__(SB) void sort_rank_kernel(const int32_t* __restrict
             s_wave[w * K + k] = run;
             run += c;
         }
+        int before = 0, total = run;
+        if (hist) {
+            total = 0;
+            for (int b = 0; b < nblk; ++b) {
+                int h = hist[(size_t)b * K + k];
+                if (b < blk) before += h;
+                total += h;
+            }
+        }
+        s_base[k] = before;
+        s_total[k] = total;
+    }
+    __syncthreads();
+    if (tid == 0) {                          // exclusive scan over slots (K <= 256)
+        int run = 0;
+        for (int k = 0; k < K; ++k) {
+            int tot = s_total[k];
+            if (blk == 0) offsets[k] = run;
+            s_base[k] += run;
+            run += tot;
+        }
+        if (blk == 0) offsets[K] = run;
     }
     __syncthreads();
     if (live) {
@@ -190,8 +218,10 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ 
 int smoe_launch_importance(const smoe_layer* L, const int32_t* orig_expert, const float* orig_gate,
                            const float* xnorm, int T, int32_t* count, float* gsum, float* score,
                            int accumulate, hipStream_t s) {
-    hipLaunchKernelGGL(importance_kernel, dim3(L->cfg.E), dim3(IMP_THREADS), 0, s, orig_expert,
-                       orig_gate, xnorm, L->expert_norm, T, count, gsum, score, accumulate);
+    const int nblk = T > 0 ? (T + IMP_THREADS - 1) / IMP_THREADS : 1;
+    hipLaunchKernelGGL(importance_kernel, dim3(nblk), dim3(IMP_THREADS), 0, s, orig_expert, orig_gate, xnorm,
+                       L->expert_norm, T, L->cfg.E, L->d_imp_partial, L->d_imp_ticket, count, gsum, score,
+                       accumulate);
     return smoe_check_hip(hipGetLastError(), "smoe_importance launch");
 }
 
@@ -199,10 +229,11 @@ int smoe_launch_permute(const smoe_layer* L, const void* x, const int32_t* slot,
                         int32_t* perm, int32_t* inv_perm, int32_t* offsets, hipStream_t s) {
     const int K = L->cfg.K;
     const int nblk = T > 0 ? smoe_sort_blocks(T) : 1;       // T = 0 still writes offsets = 0
-    hipLaunchKernelGGL(sort_hist_kernel, dim3(nblk), dim3(SB), K * sizeof(int32_t), s, slot, T, K,
-                       L->d_sort_hist);
+    if (nblk > 1)
+        hipLaunchKernelGGL(sort_hist_kernel, dim3(nblk), dim3(SB), K * sizeof(int32_t), s, slot, T, K,
+                           L->d_sort_hist);
     hipLaunchKernelGGL(sort_rank_kernel, dim3(nblk), dim3(SB), (2 + SB_WAVES) * K * sizeof(int32_t), s,
-                       slot, T, K, nblk, L->d_sort_hist, perm, inv_perm, offsets);
+                       slot, T, K, nblk, nblk > 1 ? L->d_sort_hist : nullptr, perm, inv_perm, offsets);
     if (T > 0) {
         int cpr = (int)((size_t)L->cfg.d_model * smoe_elem_size(L->cfg.dtype) / 16);
         size_t total = (size_t)T * cpr;

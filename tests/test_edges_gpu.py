@@ -1,0 +1,155 @@
+"""GPU edge cases of the C ABI: empty and tiny inputs, empty segments, one
+slot, handle state rules, slot refresh and replacement -- each against the
+oracle, same tolerances as test_parity_gpu.py."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2308_15030_amd import workloads as wl
+from harness import Case, max_abs_rel, to_dev, to_host, values
+
+pytestmark = pytest.mark.gpu
+
+
+def cfg_of(**kw):
+    base = dict(E=8, K=4, d_model=64, d_ff=96, T=100, dtype=wl.BF16, seed=21)
+    base.update(kw)
+    return wl.MoEConfig("edge", **base)
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+def test_zero_and_one_token(dtype):
+    c = Case(cfg_of(dtype=dtype, T=1), router_scale=20.0)
+    L = c.L
+    # T = 0: every call is a legal no-op; permute still writes offsets = 0
+    L.offsets.fill_(-7)
+    L.route(c.d_x, 0); L.importance(0, 0); L.permute(c.d_x, 0); L.expert_ffn(0); L.combine(0)
+    torch.cuda.synchronize()
+    assert to_host(L.offsets).tolist() == [0] * (c.cfg.K + 1)
+    assert to_host(L.count).sum() == 0 and to_host(L.score).sum() == 0
+    # T = 1
+    ref = oracle.layer_forward(c.x, c.Wr, *c.slot_weights_host(), c.e2s)
+    out = L.forward(c.d_x, 1, accumulate=0)
+    torch.cuda.synchronize()
+    assert to_host(L.slot)[0] == ref["slot"][0]
+    assert to_host(L.perm).tolist() == [0] and to_host(L.inv_perm).tolist() == [0]
+    assert np.array_equal(to_host(L.offsets), ref["offsets"])
+    tol = 1e-4 if dtype == wl.F32 else 2e-2
+    assert max_abs_rel(values(to_host(out), dtype), values(ref["out"], dtype)) <= tol
+    L.close()
+
+
+def test_empty_segments_and_single_busy_slot():
+    """Slots that get no token at all, and every token in one slot, with the
+    layer created for more tokens than are passed."""
+    cfg = cfg_of(T=333, K=4)
+    c = Case(cfg.scaled(T=400), router_scale=20.0)       # max_tokens = 400 > T used
+    L, T = c.L, 333
+    x = c.x[:T]
+    W1s, W2s = c.slot_weights_host()
+    for pattern in ("two-empty", "one-slot"):
+        slot = np.zeros(T, np.int32)
+        if pattern == "two-empty":
+            slot[::3] = 2                                  # slots 1 and 3 stay empty
+        else:
+            slot[:] = 3
+        xp, perm, inv, offsets = oracle.permute(x, slot, cfg.K)
+        L.slot[:T].copy_(to_dev(slot))
+        L.permute(c.d_x, T)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_host(L.offsets), offsets)
+        assert np.array_equal(to_host(L.perm)[:T], perm)
+        assert np.array_equal(to_host(L.inv_perm)[:T], inv)
+        assert np.array_equal(to_host(L.x_perm)[:T], xp)
+        y = oracle.expert_ffn(xp, W1s, W2s, offsets)
+        L.expert_ffn(T)
+        torch.cuda.synchronize()
+        assert max_abs_rel(values(to_host(L.y_perm)[:T], cfg.dtype), y) <= 2e-2
+    L.close()
+
+
+def test_state_rules_and_slot_replacement():
+    from paper_2308_15030_amd import binding as b
+    cfg = cfg_of(T=64, K=2, E=6)
+    c = Case(cfg, bank_experts=range(cfg.E), router_scale=20.0)
+    L = c.L
+    # a fresh handle bound to real buffers refuses route until both slots are filled
+    L2 = b.Layer(cfg.E, cfg.K, cfg.d_model, cfg.d_ff, cfg.T, cfg.dtype, router_w=torch.from_numpy(c.Wr))
+    with pytest.raises(b.SmoeError) as e:
+        L2.route(c.d_x, cfg.T)
+    assert e.value.status == b.SMOE_ESTATE
+    L2.set_resident(0, 4, c.d_W1[4], c.d_W2[4])
+    with pytest.raises(b.SmoeError):
+        L2.expert_ffn(cfg.T)
+    with pytest.raises(b.SmoeError) as e:
+        L2.set_resident(1, 4, c.d_W1[4], c.d_W2[4])        # already resident in slot 0
+    assert e.value.status == b.SMOE_ESTATE
+    L2.set_resident(1, 1, c.d_W1[1], c.d_W2[1])
+    L2.set_resident(0, 4, c.d_W1[4], c.d_W2[4])            # refresh of the same slot is legal
+    s2e, e2s = L2.maps()
+    assert s2e.tolist() == [4, 1] and e2s.tolist() == [-1, 1, -1, -1, 0, -1]
+    L2.expert_norm.copy_(L.expert_norm)
+    ref = oracle.layer_forward(c.x, c.Wr, c.W1_bank[[4, 1]], c.W2_bank[[4, 1]], e2s)
+    out = L2.forward(c.d_x, cfg.T, accumulate=0)
+    torch.cuda.synchronize()
+    ok = ~ref["ambiguous"]
+    assert np.array_equal(to_host(L2.slot)[ok], ref["slot"][ok])
+    assert max_abs_rel(values(to_host(out), cfg.dtype)[ok], values(ref["out"], cfg.dtype)[ok]) <= 2e-2
+    # replace the occupant of slot 1: expert 1 leaves, expert 5 enters
+    L2.set_resident(1, 5, c.d_W1[5], c.d_W2[5])
+    s2e, e2s = L2.maps()
+    assert s2e.tolist() == [4, 5] and e2s.tolist() == [-1, -1, -1, -1, 0, 1]
+    ref = oracle.layer_forward(c.x, c.Wr, c.W1_bank[[4, 5]], c.W2_bank[[4, 5]], e2s)
+    out = L2.forward(c.d_x, cfg.T, accumulate=0)
+    torch.cuda.synchronize()
+    ok = ~ref["ambiguous"]
+    assert np.array_equal(to_host(L2.slot)[ok], ref["slot"][ok])
+    assert np.array_equal(to_host(L2.orig_expert)[ok], ref["orig_expert"][ok])
+    assert max_abs_rel(values(to_host(out), cfg.dtype)[ok], values(ref["out"], cfg.dtype)[ok]) <= 2e-2
+    L2.close(); L.close()
+
+
+def test_large_sampled_c5():
+    """Switch-large-128 shape at full size (T = 16384, E = 128, K = 32): routing,
+    sort and importance in full, the FFN and the layer output on sampled rows
+    that the oracle computes one by one."""
+    cfg = wl.CONFIGS["c5"]
+    c = Case(cfg)
+    L, T = c.L, cfg.T
+    r = c.oracle_route()
+    L.route(c.d_x, T)
+    torch.cuda.synchronize()
+    ok = ~r["ambiguous"]
+    assert ok.mean() > 0.98
+    assert np.array_equal(to_host(L.orig_expert)[ok], r["orig_expert"][ok])
+    assert np.array_equal(to_host(L.slot)[ok], r["slot"][ok])
+    np.testing.assert_allclose(to_host(L.gate)[ok], r["gate"][ok], rtol=1e-5)
+    np.testing.assert_allclose(to_host(L.xnorm), r["xnorm"], rtol=1e-5)
+    # teacher-forced from here on
+    L.slot.copy_(to_dev(r["slot"])); L.orig_expert.copy_(to_dev(r["orig_expert"]))
+    L.orig_gate.copy_(to_dev(r["orig_gate"])); L.xnorm.copy_(to_dev(r["xnorm"])); L.gate.copy_(to_dev(r["gate"]))
+    st = oracle.importance(r["orig_expert"], r["orig_gate"], r["xnorm"], c.en_oracle)
+    L.importance(T, 0)
+    xp, perm, inv, offsets = oracle.permute(c.x, r["slot"], cfg.K)
+    L.permute(c.d_x, T)
+    L.expert_ffn(T)
+    L.combine(T)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(L.count), st[0])
+    np.testing.assert_allclose(to_host(L.score), st[2], rtol=1e-4)
+    assert np.array_equal(to_host(L.offsets), offsets)
+    assert np.array_equal(to_host(L.perm), perm)
+    assert np.array_equal(to_host(L.x_perm), xp)
+    rows = np.unique(np.concatenate([np.arange(0, T, 67), offsets[:-1].clip(0, T - 1),
+                                     (offsets[1:] - 1).clip(0, T - 1)])).astype(np.int32)
+    W1s, W2s = c.slot_weights_host()
+    y = oracle.expert_ffn(xp, W1s, W2s, offsets, rows=rows)
+    got = values(to_host(L.y_perm), cfg.dtype)
+    assert max_abs_rel(got[rows], y[rows]) <= 2e-2
+    # layer output for the tokens that own those rows
+    toks = perm[rows]
+    ref_out = r["gate"][toks].astype(np.float64)[:, None] * y[rows]
+    got_out = values(to_host(L.out), cfg.dtype)[toks]
+    assert max_abs_rel(got_out, ref_out) <= 2e-2
+    L.close()
