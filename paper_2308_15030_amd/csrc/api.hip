@@ -46,8 +46,6 @@ smoe_ws_layout smoe_ws_plan(const smoe_config& c) {
     // bf16 path: three bf16 pieces of every router weight, experts padded to a multiple of 32
     w.rsplit = off;
     if (c.dtype == SMOE_BF16) off = align_up(off + (size_t)((c.E + 31) / 32 * 32) * c.d_model * 2 * 3, 256);
-    w.imp = off;     off = align_up(off + (size_t)((c.max_tokens + 255) / 256) * 3 * c.E * 4, 256);
-    w.ticket = off;  off = align_up(off + 256, 256);
     w.norm = off;    off = align_up(off + (size_t)c.E * 64 * 4, 256);      // smoe_expert_norm partial sums
     w.total = off;
     return w;
@@ -123,8 +121,6 @@ int smoe_bind(smoe_layer_t* L, const float* router_w, void* slot_w1, void* slot_
     L->d_partial = (float*)(L->workspace + w.partial);
     L->d_router_split = L->workspace + w.rsplit;
     L->router_split_done = false;
-    L->d_imp_partial = (float*)(L->workspace + w.imp);
-    L->d_imp_ticket = (int32_t*)(L->workspace + w.ticket);
     L->ws_ready = false;
     L->d_norm_partial = (float*)(L->workspace + w.norm);
     std::fill(L->slot_to_expert.begin(), L->slot_to_expert.end(), -1);
@@ -254,8 +250,6 @@ int smoe_importance(smoe_layer_t* L, const int32_t* orig_expert, const float* or
     if (T > 0 && (!orig_expert || !orig_gate || !xnorm))
         return smoe_fail(SMOE_EINVAL, "smoe_importance: null input");
     if (T == 0 && accumulate == 1) return SMOE_OK;
-    rc = ensure_workspace(L, as_stream(stream));
-    if (rc) return rc;
     return smoe_launch_importance(L, orig_expert, orig_gate, xnorm, T, count, gsum, score, accumulate,
                                   as_stream(stream));
 }

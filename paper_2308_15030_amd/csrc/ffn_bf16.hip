@@ -325,6 +325,120 @@ __global__ __launch_bounds__(NW * 64, OCC) void grouped_gemm_bf16(
                                                                      ftile, xs);
 }
 
+// ---------------------------------------------------------------------------
+// Small-batch (decode) variant: row tiles of 32 tokens, nothing but weight
+// streaming.  With a handful of tokens per slot the FFN is bound by reading
+// each active slot's weights once, so the kernel is built around keeping many
+// 1-KiB weight loads in flight per wave: no LDS staging and no barrier in the
+// loop -- the token operand (32 rows) is read straight from L2 -- and the
+// operands of G reduction steps are fetched together, two groups in flight.
+//   KSPLIT = 1: the workgroup's 4 waves take 4 neighbouring feature blocks;
+//   KSPLIT = 4: they share one feature block and split the reduction four ways,
+//               meeting in LDS at the end (added in wave order: reproducible).
+// The second product (reduction length d_ff, only d_model outputs) uses
+// KSPLIT = 4 so that it, too, spreads over (slots x d_model/32) workgroups.
+template <int KSPLIT, bool FIRST>
+__global__ __launch_bounds__(256) void small_gemm_bf16(
+    const uint16_t* __restrict__ X, const uint4* __restrict__ Wp, const int32_t* __restrict__ offsets,
+    int nslots, int T, uint16_t* __restrict__ Y, int R, int N) {
+    constexpr int G = 8;                                   // reduction steps fetched together
+    constexpr bool XFRAG = !FIRST, YFRAG = FIRST, RELU = FIRST;
+    __shared__ __align__(16) float red[KSPLIT > 1 ? 3 * 16 * 64 : 1];
+    const int nfb = N >> 5, nrb = R >> 4;
+    const int ftiles = KSPLIT == 1 ? (nfb + 3) / 4 : nfb;
+    int slot, ftile, m0, m_end, pm0;
+    if (!find_item(offsets, nslots, T, 32, ftiles, blockIdx.x, slot, ftile, m0, m_end, pm0)) return;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int fb = KSPLIT == 1 ? ftile * 4 + wave : ftile;
+    const bool fb_ok = fb < nfb;
+    const int per = (nrb + KSPLIT - 1) / KSPLIT;
+    const int kb_lo = KSPLIT == 1 ? 0 : min(wave * per, nrb), kb_hi = KSPLIT == 1 ? nrb : min(kb_lo + per, nrb);
+
+    const uint4* wp = Wp + ((size_t)slot * nfb + min(fb, nfb - 1)) * nrb * 64 + lane;
+    const uint4* xp;                                       // this lane's token operand at reduction step 0
+    size_t xstep;                                          // in uint4 units per reduction step
+    if (XFRAG) {
+        xp = (const uint4*)X + ((size_t)(pm0 >> 5) * (R >> 3) + (lane >> 5)) * 32 + (lane & 31);
+        xstep = 2 * 32;
+    } else {
+        xp = (const uint4*)(X + (size_t)min(m0 + (lane & 31), m_end - 1) * R + (lane >> 5) * 8);
+        xstep = 2;
+    }
+    f32x16 acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    // two groups of G reduction steps are always in flight: while one group's
+    // MFMAs run, the next group's operands are already on their way
+    uint4 wA[G], xA[G], wB[G], xB[G];
+    auto fetch = [&](uint4 (&w)[G], uint4 (&xv)[G], int g0) {
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            const int kb = max(min(g0 + i, kb_hi - 1), 0);  // past the end: reloaded, not used
+            w[i] = wp[(size_t)kb * 64];
+            xv[i] = xp[(size_t)kb * xstep];
+        }
+    };
+    auto consume = [&](uint4 (&w)[G], uint4 (&xv)[G], int g0) {
+#pragma unroll
+        for (int i = 0; i < G; ++i)
+            if (g0 + i < kb_hi)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(w[i]), as_frag(xv[i]), acc, 0, 0, 0);
+    };
+    fetch(wA, xA, kb_lo);
+    for (int g0 = kb_lo; g0 < kb_hi; g0 += 2 * G) {
+        fetch(wB, xB, g0 + G);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(wA, xA, g0);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(wA, xA, g0 + 2 * G);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(wB, xB, g0 + G);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (KSPLIT > 1) {
+        if (wave > 0) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) red[((wave - 1) * 16 + i) * 64 + lane] = acc[i];
+        }
+        __syncthreads();
+        if (wave > 0) return;
+#pragma unroll
+        for (int w2 = 0; w2 < KSPLIT - 1; ++w2)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] += red[(w2 * 16 + i) * 64 + lane];
+    }
+    if (!fb_ok) return;
+    // accumulator register i of lane l: feature 8*(i/4) + 4*(l/32) + i%4, token l%32
+    uint16_t* ydst;
+    if (YFRAG) {
+        ydst = Y + (((size_t)(pm0 >> 5) * (N >> 3) + fb * 4) * 32 + (lane & 31)) * 8 + (lane >> 5) * 4;
+    } else {
+        const int row = m0 + (lane & 31);
+        if (row >= m_end) return;
+        ydst = Y + (size_t)row * N + fb * 32 + (lane >> 5) * 4;
+    }
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        float v0 = acc[4 * g], v1 = acc[4 * g + 1], v2 = acc[4 * g + 2], v3 = acc[4 * g + 3];
+        if (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
+        uint2 o;
+        o.x = (uint32_t)smoe_f32_to_bf16(v0) | ((uint32_t)smoe_f32_to_bf16(v1) << 16);
+        o.y = (uint32_t)smoe_f32_to_bf16(v2) | ((uint32_t)smoe_f32_to_bf16(v3) << 16);
+        *(uint2*)(ydst + (YFRAG ? g * 32 * 8 : g * 8)) = o;
+    }
+}
+
+template <int KSPLIT, bool FIRST>
+void launch_small(const uint16_t* X, const void* Wp, const int32_t* offsets, int nslots, uint16_t* Y, int R,
+                  int N, int T, hipStream_t s) {
+    int mtiles = (T + 31) / 32 + nslots;
+    int nfb = N >> 5;
+    int ftiles = KSPLIT == 1 ? (nfb + 3) / 4 : nfb;
+    dim3 grid(XCDS * ((mtiles + XCDS - 1) / XCDS) * ftiles);
+    hipLaunchKernelGGL((small_gemm_bf16<KSPLIT, FIRST>), grid, dim3(256), 0, s, X, (const uint4*)Wp, offsets,
+                       nslots, T, Y, R, N);
+}
+
 template <int AF, int MAXB, int NW, int BKT, int PD, int OCC, bool FIRST>
 void launch_gemm(const uint16_t* X, const void* Wp, const int32_t* offsets, int nslots, uint16_t* Y,
                  int R, int N, int T, hipStream_t s) {
@@ -341,12 +455,12 @@ void launch_gemm(const uint16_t* X, const void* Wp, const int32_t* offsets, int 
                            (const uint4*)Wp, offsets, nslots, T, Y, R, N);
 }
 
-constexpr int N_VARIANTS = 10;
+constexpr int N_VARIANTS = 12;
 
 template <bool FIRST>
 void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* offsets, int nslots,
                     uint16_t* Y, int R, int N, int T, hipStream_t s) {
-    if (R % 64 != 0) {       // d_model / d_ff are multiples of 32 by contract: 32-deep slices always fit
+    if (R % 64 != 0 && v < 10) {   // d_model / d_ff are multiples of 32 by contract: 32-deep slices always fit
         launch_gemm<1, 4, 4, 32, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s);
         return;
     }
@@ -360,7 +474,9 @@ void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* off
         case 6: launch_gemm<2, 2, 4, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   //  64 x 256
         case 7: launch_gemm<1, 2, 4, 64, 3, 3, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   //  64 x 128
         case 8: launch_gemm<1, 2, 4, 64, 1, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   //  64 x 128
-        default: launch_gemm<1, 1, 4, 64, 3, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;  //  32 x 128
+        case 9: launch_gemm<1, 1, 4, 64, 3, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   //  32 x 128
+        case 10: launch_small<1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;  // 32 x 128, streaming
+        default: launch_small<4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;  // 32 x 32, reduction split 4 ways
     }
 }
 
@@ -370,7 +486,8 @@ void pick_variants(const smoe_config& c, int T, int& v1, int& v2) {
     int per_slot = T / c.K;
     if (per_slot >= 96) { v1 = 4; v2 = 4; }
     else if (per_slot >= 48) { v1 = 5; v2 = 7; }
-    else { v1 = 9; v2 = 9; }
+    else if (per_slot >= 8) { v1 = 9; v2 = 9; }
+    else { v1 = 10; v2 = 11; }           // decode: a few tokens per slot, weight streaming
     const char* env = getenv("SMOE_FFN_VARIANT");
     if (env) {
         int a = -1, b = -1;

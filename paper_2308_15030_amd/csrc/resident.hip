@@ -15,11 +15,10 @@
 
 namespace {
 
-__global__ void clear_maps_kernel(int32_t* e2s, int E, int32_t* s2e, int K, int32_t* ticket) {
+__global__ void clear_maps_kernel(int32_t* e2s, int E, int32_t* s2e, int K) {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < E) e2s[i] = -1;
     if (i < K) s2e[i] = -1;
-    if (i == 0) *ticket = 0;
 }
 
 __global__ void set_map_kernel(int32_t* e2s, int32_t* s2e, int slot, int expert, int old_expert) {
@@ -109,7 +108,7 @@ __global__ void norm_finish_kernel(const float* __restrict__ partial, int n, flo
 int smoe_launch_clear_maps(const smoe_layer* L, hipStream_t s) {
     int n = L->cfg.E > L->cfg.K ? L->cfg.E : L->cfg.K;
     hipLaunchKernelGGL(clear_maps_kernel, dim3((n + 255) / 256), dim3(256), 0, s, L->d_expert_to_slot,
-                       L->cfg.E, L->d_slot_to_expert, L->cfg.K, L->d_imp_ticket);
+                       L->cfg.E, L->d_slot_to_expert, L->cfg.K);
     return smoe_check_hip(hipGetLastError(), "smoe_set_resident: map reset");
 }
 

@@ -33,8 +33,6 @@ struct smoe_layer {
     int32_t* d_sort_hist = nullptr;          // [sort blocks, K]
     void* d_hidden = nullptr;                // [max_tokens, d_ff] activations of the FFN
     float* d_partial = nullptr;              // small-T FFN: split partial sums
-    float* d_imp_partial = nullptr;          // importance: per-block partial sums [blocks][3][E]
-    int32_t* d_imp_ticket = nullptr;         // importance: blocks-finished counter (0 between calls)
     float* d_norm_partial = nullptr;         // smoe_expert_norm: [E][64] partial sums of squares
     bool ws_ready = false;                   // device maps and counters initialised since the bind
     void* d_router_split = nullptr;          // bf16 path: router weights split in three, MFMA order
@@ -44,7 +42,7 @@ struct smoe_layer {
 };
 
 struct smoe_ws_layout {
-    size_t e2s, s2e, hist, hidden, partial, rsplit, imp, ticket, norm, total;
+    size_t e2s, s2e, hist, hidden, partial, rsplit, norm, total;
 };
 smoe_ws_layout smoe_ws_plan(const smoe_config& c);
 

@@ -1,9 +1,9 @@
 // smoe_importance, smoe_permute and smoe_combine: the memory-bound steps
 // around the expert FFN.
 //
-//  * importance (SwapMoE Eq. 1): per-block partial sums in token order, added
-//    up in block order by whichever block finishes last, so the result is
-//    bit-reproducible (no floating-point atomics).
+//  * importance (SwapMoE Eq. 1): one workgroup per expert walks all T tokens
+//    and keeps those whose original choice is that expert; a fixed-shape LDS
+//    tree gives the three sums, so the result is bit-reproducible (no atomics).
 //  * permute: stable counting sort by slot in three launches -- per-block
 //    histograms, a ranking pass that turns them into exact positions with
 //    wavefront ballots (no atomics on positions, hence one unique, stable
@@ -16,60 +16,53 @@
 namespace {
 
 // ------------------------------------------------------------- importance
-// A block takes 256 consecutive tokens into LDS; thread e then walks them in
-// token order and keeps those whose original choice is expert e, which gives
-// per-block partial sums in a fixed order.  The block that finishes last (an
-// integer ticket) adds the partials block by block, again in a fixed order, so
-// the result does not depend on scheduling: no floating-point atomics.
+// One workgroup per expert walks all T tokens with coalesced, branch-free loads
+// and keeps those whose original choice is that expert; per-thread sums in
+// token order and a fixed-shape LDS tree give the three totals, so the result
+// is bit-reproducible (no atomics, no dependence on scheduling).
 constexpr int IMP_THREADS = 256;
 
 __global__ __launch_bounds__(IMP_THREADS) void importance_kernel(
     const int32_t* __restrict__ orig_expert, const float* __restrict__ orig_gate,
-    const float* __restrict__ xnorm, const float* __restrict__ expert_norm, int T, int E,
-    float* __restrict__ partial /* [blocks][3][E] */, int32_t* __restrict__ ticket,
+    const float* __restrict__ xnorm, const float* __restrict__ expert_norm, int T,
     int32_t* __restrict__ count, float* __restrict__ gsum, float* __restrict__ score, int accumulate) {
-    __shared__ int32_t s_e[IMP_THREADS];
+    __shared__ int32_t s_c[IMP_THREADS];
     __shared__ float s_g[IMP_THREADS], s_r[IMP_THREADS];
-    __shared__ int s_last;
-    const int tid = threadIdx.x, blk = blockIdx.x, nblk = gridDim.x;
-    const int t = blk * IMP_THREADS + tid;
-    s_e[tid] = t < T ? orig_expert[t] : -1;
-    const float gv = t < T ? orig_gate[t] : 0.f;
-    s_g[tid] = gv;
-    s_r[tid] = t < T ? xnorm[t] * gv : 0.f;
-    __syncthreads();
-    if (tid < E) {
-        int c = 0;
-        float g = 0.f, r = 0.f;
-        const int n = min(IMP_THREADS, T - blk * IMP_THREADS);
-        for (int i = 0; i < n; ++i) {
-            if (s_e[i] == tid) { c += 1; g += s_g[i]; r += s_r[i]; }
-        }
-        float* p = partial + (size_t)blk * 3 * E;
-        p[tid] = __int_as_float(c);
-        p[E + tid] = g;
-        p[2 * E + tid] = r;
+    const int e = blockIdx.x, tid = threadIdx.x;
+    int c = 0;
+    float g = 0.f, r = 0.f;
+    int t = tid;
+    for (; t + 3 * IMP_THREADS < T; t += 4 * IMP_THREADS) {      // four independent loads in flight
+        int e0 = orig_expert[t], e1 = orig_expert[t + IMP_THREADS], e2 = orig_expert[t + 2 * IMP_THREADS],
+            e3 = orig_expert[t + 3 * IMP_THREADS];
+        float g0 = orig_gate[t], g1 = orig_gate[t + IMP_THREADS], g2 = orig_gate[t + 2 * IMP_THREADS],
+              g3 = orig_gate[t + 3 * IMP_THREADS];
+        float x0 = xnorm[t], x1 = xnorm[t + IMP_THREADS], x2 = xnorm[t + 2 * IMP_THREADS],
+              x3 = xnorm[t + 3 * IMP_THREADS];
+        c += (e0 == e) + (e1 == e) + (e2 == e) + (e3 == e);
+        g += e0 == e ? g0 : 0.f; r += e0 == e ? x0 * g0 : 0.f;
+        g += e1 == e ? g1 : 0.f; r += e1 == e ? x1 * g1 : 0.f;
+        g += e2 == e ? g2 : 0.f; r += e2 == e ? x2 * g2 : 0.f;
+        g += e3 == e ? g3 : 0.f; r += e3 == e ? x3 * g3 : 0.f;
     }
-    __threadfence();                                   // partials visible before the ticket is taken
-    __syncthreads();
-    if (tid == 0) s_last = atomicAdd(ticket, 1) == nblk - 1;
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    if (tid < E) {
-        int c = 0;
-        float g = 0.f, r = 0.f;
-        for (int b = 0; b < nblk; ++b) {
-            const float* p = partial + (size_t)b * 3 * E;
-            c += __float_as_int(__builtin_nontemporal_load(&p[tid]));
-            g += __builtin_nontemporal_load(&p[E + tid]);
-            r += __builtin_nontemporal_load(&p[2 * E + tid]);
-        }
-        const float sc = expert_norm[tid] * r;
-        if (accumulate) { count[tid] += c; gsum[tid] += g; score[tid] += sc; }
-        else { count[tid] = c; gsum[tid] = g; score[tid] = sc; }
+    for (; t < T; t += IMP_THREADS) {
+        int e0 = orig_expert[t];
+        float g0 = orig_gate[t], x0 = xnorm[t];
+        c += e0 == e;
+        g += e0 == e ? g0 : 0.f;
+        r += e0 == e ? x0 * g0 : 0.f;
     }
-    if (tid == 0) *ticket = 0;                         // ready for the next call
+    s_c[tid] = c; s_g[tid] = g; s_r[tid] = r;
+    __syncthreads();
+    for (int w = IMP_THREADS / 2; w > 0; w >>= 1) {
+        if (tid < w) { s_c[tid] += s_c[tid + w]; s_g[tid] += s_g[tid + w]; s_r[tid] += s_r[tid + w]; }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        float sc = expert_norm[e] * s_r[0];
+        if (accumulate) { count[e] += s_c[0]; gsum[e] += s_g[0]; score[e] += sc; }
+        else { count[e] = s_c[0]; gsum[e] = s_g[0]; score[e] = sc; }
+    }
 }
 
 // ------------------------------------------------------------- permute
@@ -218,10 +211,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ 
 int smoe_launch_importance(const smoe_layer* L, const int32_t* orig_expert, const float* orig_gate,
                            const float* xnorm, int T, int32_t* count, float* gsum, float* score,
                            int accumulate, hipStream_t s) {
-    const int nblk = T > 0 ? (T + IMP_THREADS - 1) / IMP_THREADS : 1;
-    hipLaunchKernelGGL(importance_kernel, dim3(nblk), dim3(IMP_THREADS), 0, s, orig_expert, orig_gate, xnorm,
-                       L->expert_norm, T, L->cfg.E, L->d_imp_partial, L->d_imp_ticket, count, gsum, score,
-                       accumulate);
+    hipLaunchKernelGGL(importance_kernel, dim3(L->cfg.E), dim3(IMP_THREADS), 0, s, orig_expert,
+                       orig_gate, xnorm, L->expert_norm, T, count, gsum, score, accumulate);
     return smoe_check_hip(hipGetLastError(), "smoe_importance launch");
 }
 
