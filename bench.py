@@ -1,22 +1,29 @@
 #!/usr/bin/env python3
 """Throughput of the Virtual-Expert MoE layer hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c5|c4]
 
-One "step" is one pass of the whole hot path (route, importance, permute,
-expert FFN, combine) through every stacked MoE layer of the workload, on
-synthetic inputs already resident in HBM.  The default workload is the
-Switch-base-64 prefill shape (E=64, K=16 resident, d_model=768, d_ff=3072,
-T=4096 tokens, 6 stacked layers with independent weights, bf16), the shape the
-headline metric is quoted on.  Layer l+1 reads layer l's output plus the
-residual stream, so the six layers' 906 MB of resident weights are walked in
-turn and no layer's weights stay cache-resident between uses.
+Prefill workloads (c2, c3, c5): one "step" is one pass of the whole hot path
+(route, importance, permute, expert FFN, combine) through every stacked MoE
+layer of the workload, on synthetic inputs already resident in HBM.  The
+default, c3, is the Switch-base-64 prefill shape (E=64, K=16 resident,
+d_model=768, d_ff=3072, T=4096 tokens, 6 stacked layers with independent
+weights, bf16), the shape the headline metric is quoted on.  Layer l+1 reads
+layer l's output plus the residual stream, so the six layers' 906 MB of
+resident weights are walked in turn and no layer's weights stay cache-resident
+between uses.  `value` = T * layers / step time: tokens through a MoE layer per
+second.
 
-Prints ONE JSON line.  `value` = T * layers / step time (tokens through a MoE
-layer per second).  `roofline` is for the expert FFN's grouped-GEMM kernels:
-their duration is measured live with HIP events recorded on the launch stream
-around each of the two products of every smoe_expert_ffn call of the timed
-region.  `cpu_baseline` times the CPU oracle on one full layer of the same
+Decode workload (c4): one step is one decode step (T=32 tokens, one token per
+stream) through `--decode-layers` layers; every `period` (16) steps the
+importance scores are read back, the update policy picks the new resident set
+and the changed slots are reloaded from the full expert bank -- all of that is
+inside the timed region.  `value` = T * layers * steps / time.
+
+Prints ONE JSON line.  `roofline` is for the expert FFN's two grouped-GEMM
+launches: their duration is measured live with HIP events recorded on the
+launch stream around each product of every smoe_expert_ffn call of the timed
+region.  `cpu_baseline` times the CPU oracle on a bounded sample of the same
 workload on this machine's host cores.
 """
 import argparse
@@ -31,13 +38,45 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_MFMA_TFLOPS = 2500.0      # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per grouped-GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on
+# the default command (profiles/c3_prefill_hbm_counters.txt), mean of the two
+# launches of one FFN; None for any other configuration.
+MEASURED_TRAFFIC_C3 = 132.5e6
+
+
+def dev_t(a, dev):
+    import numpy as np
+    import torch
+    return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).to(dev)
+
+
+def make_layer(b, wl, cfg, l, experts, dev):
+    """One bound layer with `experts` (bank order) uploaded; slots 0..K-1 hold the
+    first K of them.  Returns (layer, device bank, host copies of layer data)."""
+    import torch
+    Wr = wl.router_weights(cfg, l)
+    W1, W2 = wl.expert_bank(cfg, l, experts)
+    lay = b.Layer(cfg.E, cfg.K, cfg.d_model, cfg.d_ff, cfg.T, cfg.dtype, router_w=torch.from_numpy(Wr),
+                  device=dev)
+    d1, d2 = dev_t(W1, dev), dev_t(W2, dev)
+    en = lay.expert_norm_of(d1, d2)                  # |E_i| of the experts we hold; 1 elsewhere
+    full = torch.ones(cfg.E, dtype=torch.float32, device=dev)
+    full[torch.tensor(list(experts), device=dev)] = en
+    lay.expert_norm.copy_(full)
+    for s in range(cfg.K):
+        lay.set_resident(s, int(experts[s]), d1[s], d2[s])
+    torch.cuda.synchronize()
+    return lay, (d1, d2), (Wr, W1, W2)
+
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c5"])
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--decode-layers", type=int, default=1,
+                    help="c4 only: independent layers per decode step (6 exceeds the 256 MB Infinity Cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true",
                     help="do not record per-kernel events inside the timed region")
@@ -54,99 +93,157 @@ def main():
         sys.exit("bench.py: no GPU visible")
     dev = "cuda:0"
     cfg = wl.CONFIGS[args.workload]
-    T, L = cfg.T, cfg.layers
-    s2e, e2s = wl.initial_resident(cfg)
-
-    def dev_t(a):
-        return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).to(dev)
+    decode = cfg.period > 0
+    steps = args.steps if args.steps is not None else (cfg.steps if decode else 50)
+    warmup = args.warmup if args.warmup is not None else (16 if decode else 10)
+    T = cfg.T
+    L = args.decode_layers if decode else cfg.layers
+    s2e0, e2s0 = wl.initial_resident(cfg)
+    use_events = not args.no_events
 
     t_setup = time.time()
-    layers = []
-    host_layer0 = None
+    experts = list(range(cfg.E)) if decode else list(s2e0)
+    layers, banks, host0 = [], [], None
     for l in range(L):
-        Wr = wl.router_weights(cfg, l)
-        W1, W2 = wl.expert_bank(cfg, l, s2e)
-        if l == 0:
-            host_layer0 = (Wr, W1, W2)
-        lay = b.Layer(cfg.E, cfg.K, cfg.d_model, cfg.d_ff, T, cfg.dtype, router_w=torch.from_numpy(Wr),
-                      device=dev)
-        d1, d2 = dev_t(W1), dev_t(W2)
-        en = lay.expert_norm_of(d1, d2)                  # |E_i| of the resident experts; 1 elsewhere
-        full = torch.ones(cfg.E, dtype=torch.float32, device=dev)
-        full[torch.from_numpy(s2e).to(dev).long()] = en
-        lay.expert_norm.copy_(full)
-        for s, e in enumerate(s2e):
-            lay.set_resident(s, int(e), d1[s], d2[s])
-        torch.cuda.synchronize()
-        del d1, d2
+        lay, bank, host = make_layer(b, wl, cfg, l, experts, dev)
         layers.append(lay)
-    x_host = wl.hidden_states(cfg, 0)
-    x0 = dev_t(x_host)
-    torch.cuda.synchronize()
-    print(f"[bench] {cfg.name}: {L} layers set up in {time.time() - t_setup:.1f}s", file=sys.stderr, flush=True)
+        banks.append(bank if decode else None)       # prefill never reloads: free the bank copy
+        if l == 0:
+            host0 = host
+    print(f"[bench] {cfg.name}: {L} layer(s) set up in {time.time() - t_setup:.1f}s", file=sys.stderr, flush=True)
 
-    use_events = not args.no_events
-    n_ev = args.steps * L
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n_ev)] if use_events else []
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps * L)] if use_events else []
+    active_log = []
 
-    def step(ev_base=None):
-        x = x0
-        for l, lay in enumerate(layers):
-            if ev_base is not None:
-                b.smoe_set_profile_events(lay.handle, *evs[ev_base + l])
-            # residual stream: the next layer reads x + MoE(x)
-            x = lay.forward(x, T, accumulate=1, residual=x)
-        return x
+    if not decode:
+        x_host = wl.hidden_states(cfg, 0)
+        x0 = dev_t(x_host, dev)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        step(k * L if use_events else None)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+        def step(k=None):
+            x = x0
+            for l, lay in enumerate(layers):
+                if k is not None and use_events:
+                    b.smoe_set_profile_events(lay.handle, *evs[k * L + l])
+                x = lay.forward(x, T, accumulate=1, residual=x)      # residual stream: next layer reads x + MoE(x)
+            return x
 
-    ms_per_step = dt / args.steps * 1e3
-    value = T * L / (dt / args.steps)
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(steps):
+            step(k)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+    else:
+        xs_host = wl.decode_stream(cfg, warmup + steps)
+        xs = dev_t(xs_host.reshape(-1, cfg.d_model), dev).view(warmup + steps, T, cfg.d_model)
 
-    flops_per_gemm = 2.0 * T * cfg.d_model * cfg.d_ff          # per launch; two launches per FFN
+        def reset():
+            # back to the initial resident set, so the replay sees the same sequence of updates
+            for lay, (d1, d2) in zip(layers, banks):
+                lay.rebind()
+                for s in range(cfg.K):
+                    lay.set_resident(s, s, d1[s], d2[s])
+            torch.cuda.synchronize()
+
+        def run(first, n, timed, log_active=False):
+            swaps = 0
+            for i in range(n):
+                sidx = first + i
+                x = xs[sidx]
+                for l, lay in enumerate(layers):
+                    if timed and use_events:
+                        b.smoe_set_profile_events(lay.handle, *evs[i * L + l])
+                    x = lay.forward(x, T, accumulate=0 if sidx % cfg.period == 0 else 1, residual=x)
+                    if log_active:
+                        off = lay.offsets.cpu().numpy()
+                        active_log.append(int((np.diff(off) > 0).sum()))
+                if (sidx + 1) % cfg.period == 0:
+                    for lay, (d1, d2) in zip(layers, banks):
+                        score = lay.score.cpu().numpy()              # the one host read-back per period
+                        for sl, ex in lay.select_resident(score):
+                            lay.set_resident(sl, ex, d1[ex], d2[ex])
+                            swaps += 1
+            torch.cuda.synchronize()
+            return swaps
+
+        run(0, warmup, False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        swaps = run(warmup, steps, True)
+        dt = time.perf_counter() - t0
+        # untimed replay of the same steps from the same state, to count active slots per FFN call
+        reset()
+        run(0, warmup, False)
+        run(warmup, steps, False, log_active=True)
+
+    ms_per_step = dt / steps * 1e3
+    value = T * L / (dt / steps)
+
     roof = None
     if use_events:
         g1 = np.array([e[0].elapsed_time(e[1]) for e in evs]) * 1e-3
         g2 = np.array([e[1].elapsed_time(e[2]) for e in evs]) * 1e-3
         avg = (g1.mean() + g2.mean()) / 2.0                    # mean duration of one grouped-GEMM launch
-        achieved = flops_per_gemm / avg / 1e12
-        roof = {"bound": "mfma", "kernel": "grouped_gemm_bf16 (both FFN products)",
-                "achieved": round(achieved, 2), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": None,
-                "us_gemm1": round(g1.mean() * 1e6, 2), "us_gemm2": round(g2.mean() * 1e6, 2),
-                "flop_per_launch": flops_per_gemm}
-        # the same two launches against the HBM roof: resident weights once, x in, h out+in, y out
-        bytes_ffn = 2.0 * (cfg.K * 2 * cfg.d_model * cfg.d_ff + 2 * T * cfg.d_model + 2 * T * cfg.d_ff)
-        roof["hbm_GBs_ffn"] = round(bytes_ffn / (g1.mean() + g2.mean()) / 1e9, 1)
-        roof["hbm_frac_ffn"] = round(roof["hbm_GBs_ffn"] / PEAK_HBM_GBS, 4)
+        if not decode:
+            flops = 2.0 * T * cfg.d_model * cfg.d_ff           # per launch; two launches per FFN
+            achieved = flops / avg / 1e12
+            bytes_launch = 2.0 * (cfg.K * cfg.d_model * cfg.d_ff + T * cfg.d_model + T * cfg.d_ff)
+            roof = {"bound": "mfma", "kernel": "grouped_gemm_bf16 (mean of the FFN's two launches)",
+                    "achieved": round(achieved, 2), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 4),
+                    "traffic": MEASURED_TRAFFIC_C3 if (args.workload == "c3" and steps * L >= 6) else None,
+                    "us_per_launch": round(avg * 1e6, 2), "us_gemm1": round(g1.mean() * 1e6, 2),
+                    "us_gemm2": round(g2.mean() * 1e6, 2), "flop_per_launch": flops,
+                    "hbm_bytes_per_launch_algorithmic": bytes_launch,
+                    "hbm_GBs": round(bytes_launch / avg / 1e9, 1),
+                    "hbm_frac": round(bytes_launch / avg / 1e9 / PEAK_HBM_GBS, 4)}
+        else:
+            act = float(np.mean(active_log)) if active_log else float(cfg.K)
+            bytes_launch = 2.0 * act * cfg.d_model * cfg.d_ff  # one weight matrix of every active slot
+            achieved = bytes_launch / avg / 1e9
+            roof = {"bound": "hbm", "kernel": "small_gemm_bf16 (mean of the FFN's two launches)",
+                    "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None,
+                    "us_per_launch": round(avg * 1e6, 2), "us_gemm1": round(g1.mean() * 1e6, 2),
+                    "us_gemm2": round(g2.mean() * 1e6, 2), "mean_active_slots": round(act, 2),
+                    "hbm_bytes_per_launch_algorithmic": bytes_launch}
 
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        Wr, W1, W2 = host_layer0
-        t1 = time.perf_counter()
-        oracle.layer_forward(x_host, Wr, W1, W2, e2s)
-        tc = time.perf_counter() - t1
-        cpu = {"value": round(T / tc, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
-               "kind": "oracle", "sample": f"one full layer (layer 0) of {cfg.name}, all {T} tokens, "
-                                           f"{tc:.2f}s wall"}
+        Wr, W1, W2 = host0
+        if not decode:
+            t1 = time.perf_counter()
+            oracle.layer_forward(x_host, Wr, W1[:cfg.K], W2[:cfg.K], e2s0)
+            tc = time.perf_counter() - t1
+            cpu = {"value": round(T / tc, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
+                   "kind": "oracle", "sample": f"one full layer (layer 0) of {cfg.name}, all {T} tokens, "
+                                               f"{tc:.2f}s wall"}
+        else:
+            n = min(steps, 64)
+            t1 = time.perf_counter()
+            for i in range(n):
+                oracle.layer_forward(xs_host[i], Wr, W1[:cfg.K], W2[:cfg.K], e2s0)
+            tc = time.perf_counter() - t1
+            cpu = {"value": round(T * n / tc, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
+                   "kind": "oracle", "sample": f"{n} decode steps of layer 0 of {cfg.name} on the initial "
+                                               f"resident set (no updates), {tc:.2f}s wall"}
 
+    config = {"workload": cfg.name, "E": cfg.E, "K": cfg.K, "d_model": cfg.d_model, "d_ff": cfg.d_ff,
+              "tokens": T, "layers": L,
+              "step": "route+importance+permute+expert_ffn+combine over all layers"}
+    if decode:
+        config.update(update_period=cfg.period, experts_swapped=swaps,
+                      step="one decode step: route+importance+permute+expert_ffn+combine, plus score "
+                           "read-back, policy and slot reloads every update_period steps")
     out = {
         "metric": "MoE-layer tokens/sec (Virtual-Expert top-1 layer forward)", "value": round(value, 1),
-        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if cfg.dtype == wl.BF16 else "f32", "data": "synthetic",
-        "config": {"workload": cfg.name, "E": cfg.E, "K": cfg.K, "d_model": cfg.d_model,
-                   "d_ff": cfg.d_ff, "tokens": T, "layers": L,
-                   "step": "route+importance+permute+expert_ffn+combine over all layers"},
-        "us_per_layer": round(ms_per_step * 1e3 / L, 2),
+        "config": config, "us_per_layer": round(ms_per_step * 1e3 / L, 2),
         "roofline": roof, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

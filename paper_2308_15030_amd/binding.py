@@ -214,6 +214,10 @@ class Layer:
         self.y_perm = torch.empty(T, d_model, dtype=act, device=dev)
         self.out = torch.empty(T, d_model, dtype=act, device=dev)
 
+    def rebind(self):
+        """Binds the same buffers again: every slot becomes empty."""
+        smoe_bind(self.handle, self.router_w, self.slot_w1, self.slot_w2, self.expert_norm, self.workspace)
+
     def close(self):
         if self.handle is not None:
             smoe_destroy(self.handle)
