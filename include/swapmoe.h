@@ -134,7 +134,7 @@ int smoe_get_maps(const smoe_layer_t* layer, int32_t* slot_to_expert /*host*/,
 int smoe_select_resident(const smoe_layer_t* layer, const float* score /*host*/,
                          int32_t* changed_slots /*host*/, int32_t* changed_experts /*host*/);
 
-/* Router (Background: G(x), "the i-th expert with max G(x)_i is activated")
+/* Router (Background section: with k = 1 only the expert with the largest G(x)_i runs)
  * and Masked Gating (Section 3.1).  For each token t of x [T, d_model]:
  *   logit = x_t . router_w^T (fp32), p = softmax(logit) over all E;
  *   orig_expert[t] = argmax_e logit (lowest id on a tie), orig_gate[t] = p[orig];

@@ -92,7 +92,7 @@ extern "C" {
 //
 // logit[t][e] = sum_j x[t][j] * Wr[e][j]; p = softmax over ALL E experts;
 // e* = argmax_e logit (lowest index on an exact tie), g* = p[e*]
-// (Background: "only the i-th expert with max G(x)_i is activated").
+// (Background section: with k = 1 only the expert with the largest G(x)_i runs).
 // Masked Gating (Section 3.1, Figure 4(b)): s = argmax over resident experts
 // only (expert_to_slot[e] >= 0) of the same logits, slot = expert_to_slot[s].
 // Reading: gate = p[s] from the softmax over all E (gate_mode 0, "FULL"), or
