@@ -172,8 +172,24 @@ int smoe_permute(smoe_layer_t* layer, const void* x, const int32_t* slot, int T,
 int smoe_expert_ffn(smoe_layer_t* layer, const void* x_perm, const int32_t* offsets, int T,
                     void* y_perm, void* stream);
 
+/* The whole layer in one call (bf16 layers): the same results as smoe_route,
+ * smoe_importance, smoe_permute, smoe_expert_ffn and smoe_combine issued in that
+ * order on the same buffers -- bit for bit -- in four launches instead of nine:
+ * the router also counts tokens per slot, one launch ranks the tokens and
+ * reduces the importance sums, the first FFN product reads its rows from x
+ * through perm (x_perm is never written) and the second writes
+ * gate * y (+ residual) straight to out in token order (y_perm is never
+ * written).  All the per-token and per-expert outputs of the individual calls
+ * are produced: orig_expert, orig_gate, slot, gate, xnorm [T]; count, gsum,
+ * score [E] (accumulate as in smoe_importance); perm, inv_perm [T];
+ * offsets [K+1].  residual may be NULL and may alias x; out must not alias x. */
+int smoe_forward(smoe_layer_t* layer, const void* x, int T, const void* residual, void* out,
+                 int accumulate, int32_t* orig_expert, float* orig_gate, int32_t* slot, float* gate,
+                 float* xnorm, int32_t* count, float* gsum, float* score, int32_t* perm,
+                 int32_t* inv_perm, int32_t* offsets, void* stream);
+
 /* Measurement aid (not part of the paper's method): HIP events the NEXT
- * smoe_expert_ffn call on this handle records on its stream -- ev_begin before
+ * smoe_expert_ffn (or smoe_forward) call on this handle records on its stream -- ev_begin before
  * the first product, ev_mid between the two products, ev_end after the second
  * -- so each kernel's duration can be read with hipEventElapsedTime.  The
  * events are caller-owned hipEvent_t values passed as void*; they are used

@@ -53,6 +53,7 @@ _SIGS = {
     "smoe_expert_ffn": (C.c_int, [_vp, _vp, _vp, _i, _vp, _vp]),
     "smoe_combine": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _i, _vp, _vp]),
     "smoe_set_profile_events": (C.c_int, [_vp, _vp, _vp, _vp]),
+    "smoe_forward": (C.c_int, [_vp, _vp, _i, _vp, _vp, _i] + [_vp] * 12),
 }
 EXPORTS = tuple(_SIGS)
 for _name, (_res, _args) in _SIGS.items():
@@ -152,6 +153,13 @@ def smoe_expert_ffn(layer, x_perm, offsets, T, y_perm, stream=None):
 def smoe_combine(layer, y_perm, inv_perm, gate, residual, T, out, stream=None):
     _check(_lib.smoe_combine(layer, _ptr(y_perm), _ptr(inv_perm), _ptr(gate), _ptr(residual), T,
                              _ptr(out), _stream(stream)))
+
+
+def smoe_forward(layer, x, T, residual, out, accumulate, orig_expert, orig_gate, slot, gate, xnorm, count,
+                 gsum, score, perm, inv_perm, offsets, stream=None):
+    _check(_lib.smoe_forward(layer, _ptr(x), T, _ptr(residual), _ptr(out), int(accumulate), _ptr(orig_expert),
+                             _ptr(orig_gate), _ptr(slot), _ptr(gate), _ptr(xnorm), _ptr(count), _ptr(gsum),
+                             _ptr(score), _ptr(perm), _ptr(inv_perm), _ptr(offsets), _stream(stream)))
 
 
 def smoe_set_profile_events(layer, ev_begin, ev_mid, ev_end):
@@ -271,8 +279,16 @@ class Layer:
         smoe_combine(self.handle, self.y_perm, self.inv_perm, self.gate, residual, T,
                      self.out if out is None else out)
 
+    def forward_fused(self, x, T, accumulate=1, residual=None, out=None):
+        """The whole hot path through the single-call entry point (bf16 layers)."""
+        out = self.out if out is None else out
+        smoe_forward(self.handle, x, T, residual, out, accumulate, self.orig_expert, self.orig_gate, self.slot,
+                     self.gate, self.xnorm, self.count, self.gsum, self.score, self.perm, self.inv_perm,
+                     self.offsets)
+        return out
+
     def forward(self, x, T, accumulate=1, residual=None, out=None):
-        """The whole hot path, six launches' worth of calls on the current stream."""
+        """The whole hot path as the five per-step calls on the current stream."""
         self.route(x, T)
         self.importance(T, accumulate)
         self.permute(x, T)

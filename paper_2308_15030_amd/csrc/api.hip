@@ -40,6 +40,7 @@ smoe_ws_layout smoe_ws_plan(const smoe_config& c) {
     w.e2s = off;     off = align_up(off + (size_t)c.E * 4, 256);
     w.s2e = off;     off = align_up(off + (size_t)c.K * 4, 256);
     w.hist = off;    off = align_up(off + (size_t)smoe_sort_blocks(c.max_tokens) * c.K * 4, 256);
+    w.hist32 = off;  off = align_up(off + (size_t)((c.max_tokens + 31) / 32) * c.K * 4, 256);
     // hidden activations: every segment is re-based to a multiple of 32 rows
     w.hidden = off;  off = align_up(off + ((size_t)c.max_tokens + 32 * (size_t)c.K) * c.d_ff * smoe_elem_size(c.dtype), 256);
     w.partial = off; off = align_up(off, 256);
@@ -117,6 +118,7 @@ int smoe_bind(smoe_layer_t* L, const float* router_w, void* slot_w1, void* slot_
     L->d_expert_to_slot = (int32_t*)(L->workspace + w.e2s);
     L->d_slot_to_expert = (int32_t*)(L->workspace + w.s2e);
     L->d_sort_hist = (int32_t*)(L->workspace + w.hist);
+    L->d_hist32 = (int32_t*)(L->workspace + w.hist32);
     L->d_hidden = L->workspace + w.hidden;
     L->d_partial = (float*)(L->workspace + w.partial);
     L->d_router_split = L->workspace + w.rsplit;
@@ -236,7 +238,7 @@ int smoe_route(smoe_layer_t* L, const void* x, int T, int32_t* orig_expert, floa
         if (rc) return rc;
         L->router_split_done = true;
     }
-    return smoe_launch_route(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, as_stream(stream));
+    return smoe_launch_route(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, nullptr, as_stream(stream));
 }
 
 int smoe_importance(smoe_layer_t* L, const int32_t* orig_expert, const float* orig_gate,
@@ -278,6 +280,40 @@ int smoe_expert_ffn(smoe_layer_t* L, const void* x_perm, const int32_t* offsets,
         rc = smoe_launch_ffn_f32(L, (const float*)x_perm, offsets, T, (float*)y_perm, as_stream(stream));
     else
         rc = smoe_launch_ffn_bf16(L, (const uint16_t*)x_perm, offsets, T, (uint16_t*)y_perm, as_stream(stream));
+    L->prof_ev[0] = L->prof_ev[1] = L->prof_ev[2] = nullptr;
+    return rc;
+}
+
+int smoe_forward(smoe_layer_t* L, const void* x, int T, const void* residual, void* out, int accumulate,
+                 int32_t* orig_expert, float* orig_gate, int32_t* slot, float* gate, float* xnorm,
+                 int32_t* count, float* gsum, float* score, int32_t* perm, int32_t* inv_perm,
+                 int32_t* offsets, void* stream) {
+    int rc = check_hot(L, T, "smoe_forward", true);
+    if (rc) return rc;
+    if (L->cfg.dtype != SMOE_BF16)
+        return smoe_fail(SMOE_EINVAL, "smoe_forward: only bf16 layers have the fused path; use the six calls");
+    if (accumulate != 0 && accumulate != 1)
+        return smoe_fail(SMOE_EINVAL, "smoe_forward: accumulate must be 0 or 1");
+    if (T == 0) return SMOE_OK;
+    if (!x || !out || !orig_expert || !orig_gate || !slot || !gate || !xnorm || !count || !gsum || !score ||
+        !perm || !inv_perm || !offsets)
+        return smoe_fail(SMOE_EINVAL, "smoe_forward: null buffer");
+    if (misaligned(x, 16) || misaligned(out, 16) || (residual && misaligned(residual, 16)))
+        return smoe_fail(SMOE_EINVAL, "smoe_forward: x, residual and out must be 16-byte aligned");
+    if (x == out) return smoe_fail(SMOE_EINVAL, "smoe_forward: out must not alias x");
+    hipStream_t s = as_stream(stream);
+    if (!L->router_split_done) {
+        rc = smoe_launch_split_router(L, s);
+        if (rc) return rc;
+        L->router_split_done = true;
+    }
+    rc = smoe_launch_route(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, L->d_hist32, s);
+    if (rc) return rc;
+    rc = smoe_launch_rank_importance(L, orig_expert, orig_gate, xnorm, slot, T, count, gsum, score, accumulate,
+                                     perm, inv_perm, offsets, s);
+    if (rc) return rc;
+    rc = smoe_launch_ffn_bf16_fused(L, (const uint16_t*)x, perm, offsets, gate, (const uint16_t*)residual, T,
+                                    (uint16_t*)out, s);
     L->prof_ev[0] = L->prof_ev[1] = L->prof_ev[2] = nullptr;
     return rc;
 }

@@ -122,6 +122,34 @@ __device__ __forceinline__ bf16x8 as_frag(uint4 v) {
     return c.b;
 }
 
+// Optional fusion of the permute and combine steps into the two products
+// (perm == nullptr: plain products on x_perm / y_perm).
+//   first product:  row r of the sorted order is read from x[perm[r]] (no x_perm);
+//   second product: row r is written to out[perm[r]] = gate[perm[r]] * y (+ residual[perm[r]]),
+//                   i.e. y = G(x)_i E_i(x) lands in token order (no y_perm).
+struct FuseArgs {
+    const int32_t* perm;
+    const float* gate;
+    const uint16_t* residual;
+};
+
+// Fused combine on 4 consecutive outputs of one token.  The product is first
+// rounded to bf16 exactly as the unfused path stores y_perm, so both paths give
+// the same bits; then out = gate * y (+ residual) in fp32 with one final rounding.
+__device__ __forceinline__ void apply_gate(float& v0, float& v1, float& v2, float& v3, float g,
+                                           const uint16_t* res, bool fused) {
+    if (!fused) return;
+    v0 = smoe_bf16_to_f32(smoe_f32_to_bf16(v0)); v1 = smoe_bf16_to_f32(smoe_f32_to_bf16(v1));
+    v2 = smoe_bf16_to_f32(smoe_f32_to_bf16(v2)); v3 = smoe_bf16_to_f32(smoe_f32_to_bf16(v3));
+    if (res) {
+        uint2 r = *(const uint2*)res;
+        v0 = fmaf(g, v0, __uint_as_float(r.x << 16)); v1 = fmaf(g, v1, __uint_as_float(r.x & 0xFFFF0000u));
+        v2 = fmaf(g, v2, __uint_as_float(r.y << 16)); v3 = fmaf(g, v3, __uint_as_float(r.y & 0xFFFF0000u));
+    } else {
+        v0 *= g; v1 *= g; v2 *= g; v3 *= g;
+    }
+}
+
 // One workgroup tile with NBF live token blocks.  Everything is compile-time
 // shaped: no branch inside the reduction loop.
 //   AF    feature blocks per wave          NW    waves per workgroup
@@ -131,7 +159,8 @@ __device__ __forceinline__ bf16x8 as_frag(uint4 v) {
 template <int AF, int NBF, int NW, int BKT, int PD, bool XFRAG, bool YFRAG, bool RELU>
 __device__ __forceinline__ void run_tile(const uint16_t* __restrict__ X, const uint4* __restrict__ Wp,
                                          uint16_t* __restrict__ Y, int R, int N, int slot, int m0,
-                                         int m_end, int pm0, int ftile, uint16_t* xs, int stage_elems) {
+                                         int m_end, int pm0, int ftile, uint16_t* xs, int stage_elems,
+                                         const FuseArgs fz) {
     constexpr int THREADS = NW * 64;
     constexpr int KS = BKT / 16;
     constexpr int LDR = BKT + KPAD;
@@ -162,7 +191,9 @@ __device__ __forceinline__ void run_tile(const uint16_t* __restrict__ X, const u
             tdst[i] = idx * 8;
         } else {
             int r = idx / CPR, c = idx % CPR;
-            tsrc[i] = X + (size_t)min(m0 + r, m_end - 1) * R + c * 8;
+            int row = min(m0 + r, m_end - 1);
+            if (fz.perm) row = fz.perm[row];
+            tsrc[i] = X + (size_t)row * R + c * 8;
             tdst[i] = r * LDR + c * 8;
         }
     }
@@ -273,18 +304,26 @@ __device__ __forceinline__ void run_tile(const uint16_t* __restrict__ X, const u
 #pragma unroll
         for (int b = 0; b < NBF; ++b) {
             uint16_t* ydst;
+            const uint16_t* rsrc = nullptr;
+            float gmul = 1.f;
             if (YFRAG) {   // unit [(pm0/32 + b)][(fb0+a)*4 + g][lane%32], 8 bytes at half (lane/32)
                 ydst = Y + (((size_t)((pm0 >> 5) + b) * (N >> 3) + (fb0 + a) * 4) * 32 + (lane & 31)) * 8 +
                        (lane >> 5) * 4;
             } else {
-                const int row = m0 + b * 32 + (lane & 31);
+                int row = m0 + b * 32 + (lane & 31);
                 if (row >= m_end) continue;
+                if (fz.perm) {
+                    row = fz.perm[row];
+                    gmul = fz.gate[row];
+                    if (fz.residual) rsrc = fz.residual + (size_t)row * N + (fb0 + a) * 32 + (lane >> 5) * 4;
+                }
                 ydst = Y + (size_t)row * N + (fb0 + a) * 32 + (lane >> 5) * 4;
             }
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 float v0 = acc[a][b][4 * g], v1 = acc[a][b][4 * g + 1], v2 = acc[a][b][4 * g + 2],
                       v3 = acc[a][b][4 * g + 3];
+                if (!YFRAG) apply_gate(v0, v1, v2, v3, gmul, rsrc ? rsrc + g * 8 : nullptr, fz.perm != nullptr);
                 if (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
                 uint2 o;
                 o.x = (uint32_t)smoe_f32_to_bf16(v0) | ((uint32_t)smoe_f32_to_bf16(v1) << 16);
@@ -299,14 +338,14 @@ template <int AF, int NBF, int MAXB, int NW, int BKT, int PD, bool XFRAG, bool Y
 struct TileSwitch {
     static __device__ __forceinline__ void go(int nbf, const uint16_t* X, const uint4* Wp, uint16_t* Y, int R,
                                               int N, int slot, int m0, int m_end, int pm0, int ftile,
-                                              uint16_t* xs) {
+                                              uint16_t* xs, const FuseArgs fz) {
         constexpr int stage = MAXB * 32 * (BKT + KPAD);
         if (nbf == NBF)
             run_tile<AF, NBF, NW, BKT, PD, XFRAG, YFRAG, RELU>(X, Wp, Y, R, N, slot, m0, m_end, pm0, ftile, xs,
-                                                               stage);
+                                                               stage, fz);
         else if constexpr (NBF > 1)
             TileSwitch<AF, NBF - 1, MAXB, NW, BKT, PD, XFRAG, YFRAG, RELU>::go(nbf, X, Wp, Y, R, N, slot, m0,
-                                                                              m_end, pm0, ftile, xs);
+                                                                              m_end, pm0, ftile, xs, fz);
     }
 };
 
@@ -315,14 +354,14 @@ struct TileSwitch {
 template <int AF, int MAXB, int NW, int BKT, int PD, int OCC, bool FIRST>
 __global__ __launch_bounds__(NW * 64, OCC) void grouped_gemm_bf16(
     const uint16_t* __restrict__ X, const uint4* __restrict__ Wp, const int32_t* __restrict__ offsets,
-    int nslots, int T, uint16_t* __restrict__ Y, int R, int N) {
+    int nslots, int T, uint16_t* __restrict__ Y, int R, int N, const FuseArgs fz) {
     __shared__ __align__(16) uint16_t xs[2 * MAXB * 32 * (BKT + KPAD)];
     int slot, ftile, m0, m_end, pm0;
     const int ftiles = ((N >> 5) + NW * AF - 1) / (NW * AF);
     if (!find_item(offsets, nslots, T, MAXB * 32, ftiles, blockIdx.x, slot, ftile, m0, m_end, pm0)) return;
     const int nbf = min(MAXB, (m_end - m0 + 31) >> 5);    // token blocks that hold real rows
     TileSwitch<AF, MAXB, MAXB, NW, BKT, PD, !FIRST, FIRST, FIRST>::go(nbf, X, Wp, Y, R, N, slot, m0, m_end, pm0,
-                                                                     ftile, xs);
+                                                                     ftile, xs, fz);
 }
 
 // ---------------------------------------------------------------------------
@@ -340,7 +379,7 @@ __global__ __launch_bounds__(NW * 64, OCC) void grouped_gemm_bf16(
 template <int KSPLIT, bool FIRST>
 __global__ __launch_bounds__(256) void small_gemm_bf16(
     const uint16_t* __restrict__ X, const uint4* __restrict__ Wp, const int32_t* __restrict__ offsets,
-    int nslots, int T, uint16_t* __restrict__ Y, int R, int N) {
+    int nslots, int T, uint16_t* __restrict__ Y, int R, int N, const FuseArgs fz) {
     constexpr int G = 8;                                   // reduction steps fetched together
     constexpr bool XFRAG = !FIRST, YFRAG = FIRST, RELU = FIRST;
     __shared__ __align__(16) float red[KSPLIT > 1 ? 3 * 16 * 64 : 1];
@@ -348,7 +387,9 @@ __global__ __launch_bounds__(256) void small_gemm_bf16(
     const int ftiles = KSPLIT == 1 ? (nfb + 3) / 4 : nfb;
     int slot, ftile, m0, m_end, pm0;
     if (!find_item(offsets, nslots, T, 32, ftiles, blockIdx.x, slot, ftile, m0, m_end, pm0)) return;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    // the wave index as a scalar: the reduction range below must be wave-uniform in the
+    // compiler's eyes too, because an MFMA under a lane mask still runs for every lane
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int fb = KSPLIT == 1 ? ftile * 4 + wave : ftile;
     const bool fb_ok = fb < nfb;
     const int per = (nrb + KSPLIT - 1) / KSPLIT;
@@ -361,7 +402,9 @@ __global__ __launch_bounds__(256) void small_gemm_bf16(
         xp = (const uint4*)X + ((size_t)(pm0 >> 5) * (R >> 3) + (lane >> 5)) * 32 + (lane & 31);
         xstep = 2 * 32;
     } else {
-        xp = (const uint4*)(X + (size_t)min(m0 + (lane & 31), m_end - 1) * R + (lane >> 5) * 8);
+        int row = min(m0 + (lane & 31), m_end - 1);
+        if (fz.perm) row = fz.perm[row];
+        xp = (const uint4*)(X + (size_t)row * R + (lane >> 5) * 8);
         xstep = 2;
     }
     f32x16 acc;
@@ -380,9 +423,11 @@ __global__ __launch_bounds__(256) void small_gemm_bf16(
     };
     auto consume = [&](uint4 (&w)[G], uint4 (&xv)[G], int g0) {
 #pragma unroll
-        for (int i = 0; i < G; ++i)
-            if (g0 + i < kb_hi)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(w[i]), as_frag(xv[i]), acc, 0, 0, 0);
+        for (int i = 0; i < G; ++i) {
+            // steps past the end of the range multiply by a zero token operand
+            const uint4 xz = g0 + i < kb_hi ? xv[i] : make_uint4(0, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(w[i]), as_frag(xz), acc, 0, 0, 0);
+        }
     };
     fetch(wA, xA, kb_lo);
     for (int g0 = kb_lo; g0 < kb_hi; g0 += 2 * G) {
@@ -410,16 +455,24 @@ __global__ __launch_bounds__(256) void small_gemm_bf16(
     if (!fb_ok) return;
     // accumulator register i of lane l: feature 8*(i/4) + 4*(l/32) + i%4, token l%32
     uint16_t* ydst;
+    const uint16_t* rsrc = nullptr;
+    float gmul = 1.f;
     if (YFRAG) {
         ydst = Y + (((size_t)(pm0 >> 5) * (N >> 3) + fb * 4) * 32 + (lane & 31)) * 8 + (lane >> 5) * 4;
     } else {
-        const int row = m0 + (lane & 31);
+        int row = m0 + (lane & 31);
         if (row >= m_end) return;
+        if (fz.perm) {
+            row = fz.perm[row];
+            gmul = fz.gate[row];
+            if (fz.residual) rsrc = fz.residual + (size_t)row * N + fb * 32 + (lane >> 5) * 4;
+        }
         ydst = Y + (size_t)row * N + fb * 32 + (lane >> 5) * 4;
     }
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
         float v0 = acc[4 * g], v1 = acc[4 * g + 1], v2 = acc[4 * g + 2], v3 = acc[4 * g + 3];
+        if (!YFRAG) apply_gate(v0, v1, v2, v3, gmul, rsrc ? rsrc + g * 8 : nullptr, fz.perm != nullptr);
         if (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
         uint2 o;
         o.x = (uint32_t)smoe_f32_to_bf16(v0) | ((uint32_t)smoe_f32_to_bf16(v1) << 16);
@@ -430,18 +483,18 @@ __global__ __launch_bounds__(256) void small_gemm_bf16(
 
 template <int KSPLIT, bool FIRST>
 void launch_small(const uint16_t* X, const void* Wp, const int32_t* offsets, int nslots, uint16_t* Y, int R,
-                  int N, int T, hipStream_t s) {
+                  int N, int T, const FuseArgs& fz, hipStream_t s) {
     int mtiles = (T + 31) / 32 + nslots;
     int nfb = N >> 5;
     int ftiles = KSPLIT == 1 ? (nfb + 3) / 4 : nfb;
     dim3 grid(XCDS * ((mtiles + XCDS - 1) / XCDS) * ftiles);
     hipLaunchKernelGGL((small_gemm_bf16<KSPLIT, FIRST>), grid, dim3(256), 0, s, X, (const uint4*)Wp, offsets,
-                       nslots, T, Y, R, N);
+                       nslots, T, Y, R, N, fz);
 }
 
 template <int AF, int MAXB, int NW, int BKT, int PD, int OCC, bool FIRST>
 void launch_gemm(const uint16_t* X, const void* Wp, const int32_t* offsets, int nslots, uint16_t* Y,
-                 int R, int N, int T, hipStream_t s) {
+                 int R, int N, int T, const FuseArgs& fz, hipStream_t s) {
     constexpr int BT = 32 * MAXB;
     int mtiles = (T + BT - 1) / BT + nslots;               // upper bound on the row tiles of all slots
     int ftiles = ((N >> 5) + NW * AF - 1) / (NW * AF);
@@ -449,34 +502,29 @@ void launch_gemm(const uint16_t* X, const void* Wp, const int32_t* offsets, int 
     dim3 grid(XCDS * ((mtiles + XCDS - 1) / XCDS) * ftiles);
     if ((R / BKT) % (PD + 1) == 0)
         hipLaunchKernelGGL((grouped_gemm_bf16<AF, MAXB, NW, BKT, PD, OCC, FIRST>), grid, dim3(NW * 64), 0, s, X,
-                           (const uint4*)Wp, offsets, nslots, T, Y, R, N);
+                           (const uint4*)Wp, offsets, nslots, T, Y, R, N, fz);
     else   // slice count not a multiple of the ring length: same tile without weight prefetch
         hipLaunchKernelGGL((grouped_gemm_bf16<AF, MAXB, NW, BKT, 0, OCC, FIRST>), grid, dim3(NW * 64), 0, s, X,
-                           (const uint4*)Wp, offsets, nslots, T, Y, R, N);
+                           (const uint4*)Wp, offsets, nslots, T, Y, R, N, fz);
 }
 
-constexpr int N_VARIANTS = 12;
+constexpr int N_VARIANTS = 7;
 
 template <bool FIRST>
 void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* offsets, int nslots,
-                    uint16_t* Y, int R, int N, int T, hipStream_t s) {
-    if (R % 64 != 0 && v < 10) {   // d_model / d_ff are multiples of 32 by contract: 32-deep slices always fit
-        launch_gemm<1, 4, 4, 32, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s);
+                    uint16_t* Y, int R, int N, int T, const FuseArgs& fz, hipStream_t s) {
+    if (R % 64 != 0 && v < 5) {   // d_model / d_ff are multiples of 32 by contract: 32-deep slices always fit
+        launch_gemm<1, 4, 4, 32, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s);
         return;
     }
     switch (v) {             //            AF MAXB NW BKT PD OCC     tokens x features per workgroup
-        case 0: launch_gemm<2, 8, 4, 64, 1, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   // 256 x 256
-        case 1: launch_gemm<2, 4, 4, 64, 3, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   // 128 x 256
-        case 2: launch_gemm<1, 8, 4, 64, 3, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   // 256 x 128
-        case 3: launch_gemm<1, 4, 4, 64, 3, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   // 128 x 128
-        case 4: launch_gemm<1, 4, 4, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   // 128 x 128
-        case 5: launch_gemm<2, 2, 4, 64, 3, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   //  64 x 256
-        case 6: launch_gemm<2, 2, 4, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   //  64 x 256
-        case 7: launch_gemm<1, 2, 4, 64, 3, 3, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   //  64 x 128
-        case 8: launch_gemm<1, 2, 4, 64, 1, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   //  64 x 128
-        case 9: launch_gemm<1, 1, 4, 64, 3, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;   //  32 x 128
-        case 10: launch_small<1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;  // 32 x 128, streaming
-        default: launch_small<4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, s); break;  // 32 x 32, reduction split 4 ways
+        case 0: launch_gemm<2, 8, 4, 64, 1, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  // 256 x 256
+        case 1: launch_gemm<1, 4, 4, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  // 128 x 128
+        case 2: launch_gemm<2, 2, 4, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  //  64 x 256
+        case 3: launch_gemm<1, 2, 4, 64, 1, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  //  64 x 128
+        case 4: launch_gemm<1, 1, 4, 64, 3, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  //  32 x 128
+        case 5: launch_small<1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;   // 32 x 128, streaming
+        default: launch_small<4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  // 32 x 32, reduction split 4 ways
     }
 }
 
@@ -484,10 +532,10 @@ void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* off
 // built-in choice (a tuning aid; the indices are those of launch_variant).
 void pick_variants(const smoe_config& c, int T, int& v1, int& v2) {
     int per_slot = T / c.K;
-    if (per_slot >= 96) { v1 = 4; v2 = 4; }
-    else if (per_slot >= 48) { v1 = 5; v2 = 7; }
-    else if (per_slot >= 8) { v1 = 9; v2 = 9; }
-    else { v1 = 10; v2 = 11; }           // decode: a few tokens per slot, weight streaming
+    if (per_slot >= 96) { v1 = 1; v2 = 1; }
+    else if (per_slot >= 48) { v1 = 2; v2 = 3; }
+    else if (per_slot >= 8) { v1 = 4; v2 = 4; }
+    else { v1 = 5; v2 = 6; }             // decode: a few tokens per slot, weight streaming
     const char* env = getenv("SMOE_FFN_VARIANT");
     if (env) {
         int a = -1, b = -1;
@@ -506,10 +554,29 @@ int smoe_launch_ffn_bf16(const smoe_layer* L, const uint16_t* x_perm, const int3
     int v1, v2;
     pick_variants(c, T, v1, v2);
     uint16_t* h = (uint16_t*)L->d_hidden;
+    const FuseArgs none{nullptr, nullptr, nullptr};
     if (L->prof_ev[0]) (void)hipEventRecord(L->prof_ev[0], s);
-    launch_variant<true>(v1, x_perm, L->slot_w1, offsets, c.K, h, c.d_model, c.d_ff, T, s);
+    launch_variant<true>(v1, x_perm, L->slot_w1, offsets, c.K, h, c.d_model, c.d_ff, T, none, s);
     if (L->prof_ev[1]) (void)hipEventRecord(L->prof_ev[1], s);
-    launch_variant<false>(v2, h, L->slot_w2, offsets, c.K, y_perm, c.d_ff, c.d_model, T, s);
+    launch_variant<false>(v2, h, L->slot_w2, offsets, c.K, y_perm, c.d_ff, c.d_model, T, none, s);
     if (L->prof_ev[2]) (void)hipEventRecord(L->prof_ev[2], s);
     return smoe_check_hip(hipGetLastError(), "smoe_expert_ffn launch");
+}
+
+// Fused form used by smoe_forward: the first product gathers its rows from x
+// through perm, the second scatters gate * y (+ residual) to out in token order.
+int smoe_launch_ffn_bf16_fused(const smoe_layer* L, const uint16_t* x, const int32_t* perm,
+                               const int32_t* offsets, const float* gate, const uint16_t* residual, int T,
+                               uint16_t* out, hipStream_t s) {
+    const smoe_config& c = L->cfg;
+    int v1, v2;
+    pick_variants(c, T, v1, v2);
+    uint16_t* h = (uint16_t*)L->d_hidden;
+    const FuseArgs gather{perm, nullptr, nullptr}, scatter{perm, gate, residual};
+    if (L->prof_ev[0]) (void)hipEventRecord(L->prof_ev[0], s);
+    launch_variant<true>(v1, x, L->slot_w1, offsets, c.K, h, c.d_model, c.d_ff, T, gather, s);
+    if (L->prof_ev[1]) (void)hipEventRecord(L->prof_ev[1], s);
+    launch_variant<false>(v2, h, L->slot_w2, offsets, c.K, out, c.d_ff, c.d_model, T, scatter, s);
+    if (L->prof_ev[2]) (void)hipEventRecord(L->prof_ev[2], s);
+    return smoe_check_hip(hipGetLastError(), "smoe_forward: FFN launch");
 }

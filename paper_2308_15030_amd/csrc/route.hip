@@ -50,8 +50,9 @@ __global__ __launch_bounds__(THREADS) void route_kernel(
     const XT* __restrict__ x, const float* __restrict__ Wr, const int32_t* __restrict__ e2s,
     int T, int d, int E, int gate_mode,
     int32_t* __restrict__ orig_expert, float* __restrict__ orig_gate, int32_t* __restrict__ slot,
-    float* __restrict__ gate, float* __restrict__ xnorm) {
+    float* __restrict__ gate, float* __restrict__ xnorm, int32_t* __restrict__ hist32, int K) {
     extern __shared__ __align__(16) float smem[];
+    __shared__ int32_t s_slot[TB];
     constexpr int ER = 64 * NEC;                 // expert rows held in LDS
     float* xs = smem;                            // [TB][LDW]
     float* ws = smem + TB * LDW;                 // [ER][LDW]; reused as logits [TB][ER+1]
@@ -151,9 +152,20 @@ __global__ __launch_bounds__(THREADS) void route_kernel(
         float ps = expf(rbest - best);
         orig_expert[tok] = bi;
         orig_gate[tok] = 1.0f / z;
-        slot[tok] = rbi < ER ? s_e2s[rbi] : 0;   // rbi is always valid once every slot is set
+        const int sv = rbi < ER ? s_e2s[rbi] : 0;   // rbi is always valid once every slot is set
+        slot[tok] = sv;
+        s_slot[st] = sv;
         gate[tok] = gate_mode == SMOE_GATE_RENORM ? ps / zr : ps / z;
         xnorm[tok] = sqrtf(sq);
+    }
+    if (hist32) {                                 // tokens per slot in this block, for the fused sort
+        __syncthreads();
+        const int n = min(TB, T - t0);
+        for (int k = tid; k < K; k += THREADS) {
+            int c = 0;
+            for (int i = 0; i < n; ++i) c += s_slot[i] == k;
+            hist32[(size_t)blockIdx.x * K + k] = c;
+        }
     }
 }
 
@@ -216,8 +228,9 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
     const uint16_t* __restrict__ x, const uint4* __restrict__ Wsplit, const int32_t* __restrict__ e2s,
     int T, int d, int E, int gate_mode,
     int32_t* __restrict__ orig_expert, float* __restrict__ orig_gate, int32_t* __restrict__ slot,
-    float* __restrict__ gate, float* __restrict__ xnorm) {
+    float* __restrict__ gate, float* __restrict__ xnorm, int32_t* __restrict__ hist32, int K) {
     extern __shared__ __align__(16) float smem[];
+    __shared__ int32_t s_slot[RT];
     constexpr int EP = NEB * 32;
     constexpr int THREADS = NWR * 64;
     // reduction steps whose operands are fetched together, so that one memory
@@ -227,7 +240,9 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
     float* sqp = smem + NWR * EP * RTP;           // [NWR waves][2 halves][RT] partial sums of squares
     __shared__ int32_t s_e2s[EP];
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    // wave index as a scalar: loop bounds that guard MFMAs must be wave-uniform for the
+    // compiler as well (an MFMA under a lane mask still runs for every lane)
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int t0 = blockIdx.x * RT;
     for (int e = tid; e < EP; e += THREADS) s_e2s[e] = e < E ? e2s[e] : -1;
 
@@ -260,22 +275,22 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
         __builtin_amdgcn_sched_barrier(0);                    // all of the group's loads are issued first
 #pragma unroll
         for (int i = 0; i < G; ++i) {
-            if (g0 + i < kb_hi) {
-                uint32_t xw[4] = {xv[i].x, xv[i].y, xv[i].z, xv[i].w};
+            // steps past the end of the range contribute a zero token operand
+            const uint4 xz = g0 + i < kb_hi ? xv[i] : make_uint4(0, 0, 0, 0);
+            uint32_t xw[4] = {xz.x, xz.y, xz.z, xz.w};
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float a = __uint_as_float(xw[q] << 16), c = __uint_as_float(xw[q] & 0xFFFF0000u);
-                    sq = fmaf(a, a, sq);
-                    sq = fmaf(c, c, sq);
-                }
-                bf16x8 xf = frag_of(xv[i]);
-                // smallest terms first, so they are not absorbed by the large partial sums
-#pragma unroll
-                for (int s3 = 2; s3 >= 0; --s3)
-#pragma unroll
-                    for (int b = 0; b < NEB; ++b)
-                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_of(w[i][b][s3]), xf, acc[b], 0, 0, 0);
+            for (int q = 0; q < 4; ++q) {
+                float a = __uint_as_float(xw[q] << 16), c = __uint_as_float(xw[q] & 0xFFFF0000u);
+                sq = fmaf(a, a, sq);
+                sq = fmaf(c, c, sq);
             }
+            bf16x8 xf = frag_of(xz);
+            // smallest terms first, so they are not absorbed by the large partial sums
+#pragma unroll
+            for (int s3 = 2; s3 >= 0; --s3)
+#pragma unroll
+                for (int b = 0; b < NEB; ++b)
+                    acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_of(w[i][b][s3]), xf, acc[b], 0, 0, 0);
         }
     }
     // accumulator register i of lane l: expert 8*(i/4) + 4*(l/32) + i%4 (+32 per block), token l%32
@@ -290,7 +305,7 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
     __syncthreads();
 
     // epilogue: the first 256 threads, lanes 8*st .. 8*st+7 own token st
-    if (tid >= 256) return;
+    if (tid < 256) {
     const int st = tid >> 3, sub = tid & 7;
     const int tok = t0 + st;
     float best = -INFINITY, rbest = -INFINITY;
@@ -328,15 +343,27 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
         float ps = expf(rbest - best);
         orig_expert[tok] = bi;
         orig_gate[tok] = 1.0f / z;
-        slot[tok] = rbi < EP ? s_e2s[rbi] : 0;    // rbi is always valid once every slot is set
+        const int sv = rbi < EP ? s_e2s[rbi] : 0;    // rbi is always valid once every slot is set
+        slot[tok] = sv;
+        s_slot[st] = sv;
         gate[tok] = gate_mode == SMOE_GATE_RENORM ? ps / zr : ps / z;
         xnorm[tok] = sqrtf(ss);
+    }
+    }
+    if (hist32) {                                 // tokens per slot in this block, for the fused sort
+        __syncthreads();
+        const int n = min(RT, T - t0);
+        for (int k = tid; k < K; k += THREADS) {
+            int c = 0;
+            for (int i = 0; i < n; ++i) c += s_slot[i] == k;
+            hist32[(size_t)blockIdx.x * K + k] = c;
+        }
     }
 }
 
 template <int NEB>
 int launch_mfma(const smoe_layer* L, const void* x, int T, int32_t* oe, float* og, int32_t* sl, float* g,
-                float* xn, hipStream_t s) {
+                float* xn, int32_t* hist32, hipStream_t s) {
     constexpr int EP = NEB * 32;
     constexpr int NWR = NEB <= 2 ? 8 : 4;
     size_t lds = (size_t)(NWR * EP * RTP + 2 * NWR * RT) * 4;
@@ -349,13 +376,13 @@ int launch_mfma(const smoe_layer* L, const void* x, int T, int32_t* oe, float* o
     }
     hipLaunchKernelGGL(kern, dim3((T + RT - 1) / RT), dim3(NWR * 64), lds, s, (const uint16_t*)x,
                        (const uint4*)L->d_router_split, L->d_expert_to_slot, T, L->cfg.d_model, L->cfg.E,
-                       L->cfg.gate_mode, oe, og, sl, g, xn);
+                       L->cfg.gate_mode, oe, og, sl, g, xn, hist32, L->cfg.K);
     return smoe_check_hip(hipGetLastError(), "smoe_route launch");
 }
 
 template <typename XT, int NEC>
 int launch(const smoe_layer* L, const void* x, int T, int32_t* oe, float* og, int32_t* sl, float* g,
-           float* xn, hipStream_t s) {
+           float* xn, int32_t* hist32, hipStream_t s) {
     constexpr int ER = 64 * NEC;
     size_t lds_main = (size_t)(TB * LDW + ER * LDW) * 4;
     size_t lds_epi = (size_t)(TB * LDW + TB * (ER + 1)) * 4;
@@ -369,19 +396,20 @@ int launch(const smoe_layer* L, const void* x, int T, int32_t* oe, float* og, in
     }
     dim3 grid((T + TB - 1) / TB);
     hipLaunchKernelGGL(kern, grid, dim3(THREADS), lds, s, (const XT*)x, L->router_w,
-                       L->d_expert_to_slot, T, L->cfg.d_model, L->cfg.E, L->cfg.gate_mode, oe, og, sl, g, xn);
+                       L->d_expert_to_slot, T, L->cfg.d_model, L->cfg.E, L->cfg.gate_mode, oe, og, sl, g, xn,
+                       hist32, L->cfg.K);
     return smoe_check_hip(hipGetLastError(), "smoe_route launch");
 }
 
 template <typename XT>
 int dispatch(const smoe_layer* L, const void* x, int T, int32_t* oe, float* og, int32_t* sl, float* g,
-             float* xn, hipStream_t s) {
+             float* xn, int32_t* hist32, hipStream_t s) {
     int nec = (L->cfg.E + 63) / 64;
     switch (nec) {
-        case 1: return launch<XT, 1>(L, x, T, oe, og, sl, g, xn, s);
-        case 2: return launch<XT, 2>(L, x, T, oe, og, sl, g, xn, s);
-        case 3: return launch<XT, 3>(L, x, T, oe, og, sl, g, xn, s);
-        case 4: return launch<XT, 4>(L, x, T, oe, og, sl, g, xn, s);
+        case 1: return launch<XT, 1>(L, x, T, oe, og, sl, g, xn, hist32, s);
+        case 2: return launch<XT, 2>(L, x, T, oe, og, sl, g, xn, hist32, s);
+        case 3: return launch<XT, 3>(L, x, T, oe, og, sl, g, xn, hist32, s);
+        case 4: return launch<XT, 4>(L, x, T, oe, og, sl, g, xn, hist32, s);
         default: return smoe_fail(SMOE_EINVAL, "smoe_route: E=%d exceeds 256", L->cfg.E);
     }
 }
@@ -397,18 +425,19 @@ int smoe_launch_split_router(const smoe_layer* L, hipStream_t s) {
 }
 
 int smoe_launch_route(const smoe_layer* L, const void* x, int T, int32_t* orig_expert,
-                      float* orig_gate, int32_t* slot, float* gate, float* xnorm, hipStream_t s) {
+                      float* orig_gate, int32_t* slot, float* gate, float* xnorm, int32_t* hist32,
+                      hipStream_t s) {
     if (L->cfg.dtype == SMOE_F32)
-        return dispatch<float>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, s);
+        return dispatch<float>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, s);
     switch ((L->cfg.E + 31) / 32) {
-        case 1: return launch_mfma<1>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, s);
-        case 2: return launch_mfma<2>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, s);
-        case 3: return launch_mfma<3>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, s);
-        case 4: return launch_mfma<4>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, s);
-        case 5: return launch_mfma<5>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, s);
-        case 6: return launch_mfma<6>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, s);
-        case 7: return launch_mfma<7>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, s);
-        case 8: return launch_mfma<8>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, s);
+        case 1: return launch_mfma<1>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, s);
+        case 2: return launch_mfma<2>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, s);
+        case 3: return launch_mfma<3>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, s);
+        case 4: return launch_mfma<4>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, s);
+        case 5: return launch_mfma<5>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, s);
+        case 6: return launch_mfma<6>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, s);
+        case 7: return launch_mfma<7>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, s);
+        case 8: return launch_mfma<8>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, s);
         default: return smoe_fail(SMOE_EINVAL, "smoe_route: E=%d exceeds 256", L->cfg.E);
     }
 }

@@ -31,6 +31,7 @@ struct smoe_layer {
     int32_t* d_expert_to_slot = nullptr;     // [E]
     int32_t* d_slot_to_expert = nullptr;     // [K]
     int32_t* d_sort_hist = nullptr;          // [sort blocks, K]
+    int32_t* d_hist32 = nullptr;             // fused path: [ceil(max_tokens/32), K] from the router
     void* d_hidden = nullptr;                // [max_tokens, d_ff] activations of the FFN
     float* d_partial = nullptr;              // small-T FFN: split partial sums
     float* d_norm_partial = nullptr;         // smoe_expert_norm: [E][64] partial sums of squares
@@ -42,7 +43,7 @@ struct smoe_layer {
 };
 
 struct smoe_ws_layout {
-    size_t e2s, s2e, hist, hidden, partial, rsplit, norm, total;
+    size_t e2s, s2e, hist, hist32, hidden, partial, rsplit, norm, total;
 };
 smoe_ws_layout smoe_ws_plan(const smoe_config& c);
 
@@ -54,8 +55,17 @@ inline int smoe_sort_blocks(int T) { return (T + SMOE_SORT_BLOCK - 1) / SMOE_SOR
 
 // Kernel launchers, one per translation unit.  All validate nothing: the ABI
 // layer has done that.  Each returns a smoe_status.
+// hist32 (nullable): tokens per slot for every block of 32 tokens, [ceil(T/32)][K]
 int smoe_launch_route(const smoe_layer* L, const void* x, int T, int32_t* orig_expert,
-                      float* orig_gate, int32_t* slot, float* gate, float* xnorm, hipStream_t s);
+                      float* orig_gate, int32_t* slot, float* gate, float* xnorm, int32_t* hist32,
+                      hipStream_t s);
+int smoe_launch_rank_importance(const smoe_layer* L, const int32_t* orig_expert, const float* orig_gate,
+                                const float* xnorm, const int32_t* slot, int T, int32_t* count, float* gsum,
+                                float* score, int accumulate, int32_t* perm, int32_t* inv_perm,
+                                int32_t* offsets, hipStream_t s);
+int smoe_launch_ffn_bf16_fused(const smoe_layer* L, const uint16_t* x, const int32_t* perm,
+                               const int32_t* offsets, const float* gate, const uint16_t* residual, int T,
+                               uint16_t* out, hipStream_t s);
 int smoe_launch_importance(const smoe_layer* L, const int32_t* orig_expert, const float* orig_gate,
                            const float* xnorm, int T, int32_t* count, float* gsum, float* score,
                            int accumulate, hipStream_t s);

@@ -154,6 +154,109 @@ __global__ __launch_bounds__(SB) void sort_rank_kernel(const int32_t* __restrict
     }
 }
 
+// Fused launch used by smoe_forward: blocks [0, nblk) rank the tokens exactly as
+// sort_rank_kernel does, taking the per-32-token slot histograms the router
+// wrote (so no histogram launch); blocks [nblk, nblk + E) are the importance
+// reduction, one expert each.  The two halves are independent; sharing a launch
+// only saves dispatch latency.
+__global__ __launch_bounds__(SB) void rank_importance_kernel(
+    const int32_t* __restrict__ slot, int T, int K, int nblk, const int32_t* __restrict__ hist32,
+    int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm, int32_t* __restrict__ offsets,
+    const int32_t* __restrict__ orig_expert, const float* __restrict__ orig_gate,
+    const float* __restrict__ xnorm, const float* __restrict__ expert_norm,
+    int32_t* __restrict__ count, float* __restrict__ gsum, float* __restrict__ score, int accumulate) {
+    extern __shared__ int32_t sm[];
+    const int tid = threadIdx.x;
+    if ((int)blockIdx.x >= nblk) {
+        // ---- importance of expert e: the first IMP_THREADS threads repeat importance_kernel's
+        // summation order exactly (thread j takes tokens j, j+256, ...; fixed LDS tree), so the
+        // fused and the separate call give the same bits
+        const int e = blockIdx.x - nblk;
+        int32_t* s_c = sm;
+        float* s_g = (float*)(sm + IMP_THREADS);
+        float* s_r = (float*)(sm + 2 * IMP_THREADS);
+        if (tid < IMP_THREADS) {
+            int c = 0;
+            float g = 0.f, r = 0.f;
+            for (int t = tid; t < T; t += IMP_THREADS) {
+                const int e0 = orig_expert[t];
+                const float g0 = orig_gate[t], x0 = xnorm[t];
+                c += e0 == e;
+                g += e0 == e ? g0 : 0.f;
+                r += e0 == e ? x0 * g0 : 0.f;
+            }
+            s_c[tid] = c; s_g[tid] = g; s_r[tid] = r;
+        }
+        __syncthreads();
+        for (int w = IMP_THREADS / 2; w > 0; w >>= 1) {
+            if (tid < w) { s_c[tid] += s_c[tid + w]; s_g[tid] += s_g[tid + w]; s_r[tid] += s_r[tid + w]; }
+            __syncthreads();
+        }
+        if (tid == 0) {
+            const float sc = expert_norm[e] * s_r[0];
+            if (accumulate) { count[e] += s_c[0]; gsum[e] += s_g[0]; score[e] += sc; }
+            else { count[e] = s_c[0]; gsum[e] = s_g[0]; score[e] = sc; }
+        }
+        return;
+    }
+    // ---- stable rank of the tokens of sort block blk
+    int32_t* s_base = sm;                    // [K]
+    int32_t* s_total = sm + K;               // [K]
+    int32_t* s_wave = sm + 2 * K;            // [SB_WAVES][K]
+    const int blk = blockIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < (2 + SB_WAVES) * K; i += SB) sm[i] = 0;
+    __syncthreads();
+    {   // totals and "before this block" from the router's histograms (integer adds: order-free)
+        const int nrb = (T + 31) / 32, first_rb = blk * (SB / 32);
+        for (int idx = tid; idx < nrb * K; idx += SB) {
+            const int rb = idx / K, k = idx - rb * K;
+            const int h = hist32[idx];
+            if (h) {
+                atomicAdd(&s_total[k], h);
+                if (rb < first_rb) atomicAdd(&s_base[k], h);
+            }
+        }
+    }
+    const int t = blk * SB + tid;
+    int my = t < T ? slot[t] : -1;
+    const bool live = (unsigned)my < (unsigned)K;
+    if (!live) my = 0;
+    unsigned long long peers = __ballot(live);
+    for (int bit = 0; (1 << bit) < K; ++bit) {
+        unsigned long long b = __ballot(live && ((my >> bit) & 1));
+        peers &= ((my >> bit) & 1) ? b : ~b;
+    }
+    const unsigned long long below = (1ull << lane) - 1ull;
+    const int rank_in_wave = __popcll(peers & below);
+    if (live && rank_in_wave == 0) s_wave[wave * K + my] = __popcll(peers);
+    __syncthreads();
+    for (int k = tid; k < K; k += SB) {      // exclusive prefix over the waves, per slot
+        int run = 0;
+        for (int w = 0; w < SB_WAVES; ++w) {
+            int c = s_wave[w * K + k];
+            s_wave[w * K + k] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {                          // exclusive scan over slots
+        int run = 0;
+        for (int k = 0; k < K; ++k) {
+            int tot = s_total[k];
+            if (blk == 0) offsets[k] = run;
+            s_base[k] += run;
+            run += tot;
+        }
+        if (blk == 0) offsets[K] = run;
+    }
+    __syncthreads();
+    if (live) {
+        int pos = s_base[my] + s_wave[wave * K + my] + rank_in_wave;
+        perm[pos] = t;
+        inv_perm[t] = pos;
+    }
+}
+
 // x_perm[pos, :] = x[perm[pos], :], 16 bytes per thread.
 __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restrict__ x,
                                                           const int32_t* __restrict__ perm, int T,
@@ -232,6 +335,20 @@ int smoe_launch_permute(const smoe_layer* L, const void* x, const int32_t* slot,
                            (const uint4*)x, perm, T, cpr, (uint4*)x_perm);
     }
     return smoe_check_hip(hipGetLastError(), "smoe_permute launch");
+}
+
+int smoe_launch_rank_importance(const smoe_layer* L, const int32_t* orig_expert, const float* orig_gate,
+                                const float* xnorm, const int32_t* slot, int T, int32_t* count, float* gsum,
+                                float* score, int accumulate, int32_t* perm, int32_t* inv_perm,
+                                int32_t* offsets, hipStream_t s) {
+    const int K = L->cfg.K, E = L->cfg.E;
+    const int nblk = smoe_sort_blocks(T);
+    size_t lds = (size_t)(2 + SB_WAVES) * K * sizeof(int32_t);
+    if (lds < 3 * IMP_THREADS * sizeof(int32_t)) lds = 3 * IMP_THREADS * sizeof(int32_t);
+    hipLaunchKernelGGL(rank_importance_kernel, dim3(nblk + E), dim3(SB), lds, s, slot, T, K, nblk, L->d_hist32,
+                       perm, inv_perm, offsets, orig_expert, orig_gate, xnorm, L->expert_norm, count, gsum,
+                       score, accumulate);
+    return smoe_check_hip(hipGetLastError(), "smoe_forward: sort/importance launch");
 }
 
 int smoe_launch_combine(const smoe_layer* L, const void* y_perm, const int32_t* inv_perm,

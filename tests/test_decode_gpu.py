@@ -20,7 +20,8 @@ pytestmark = pytest.mark.gpu
 STEPS = 64
 
 
-def test_decode_with_updates():
+@pytest.mark.parametrize("fused", [False, True])
+def test_decode_with_updates(fused):
     cfg = wl.CONFIGS["c4"]
     c = Case(cfg, bank_experts=range(cfg.E), x=np.zeros((cfg.T, cfg.d_model), np.uint16))
     L, T, K = c.L, cfg.T, cfg.K
@@ -33,7 +34,8 @@ def test_decode_with_updates():
     for step in range(STEPS):
         first = step % cfg.period == 0
         # ---- library, free-running
-        out = L.forward(d_xs[step], T, accumulate=0 if first else 1)
+        fwd = L.forward_fused if fused else L.forward
+        out = fwd(d_xs[step], T, accumulate=0 if first else 1)
         torch.cuda.synchronize()
         # ---- oracle on the same input and the same resident set
         idx = [c.bank_pos[int(e)] for e in s2e]

@@ -184,3 +184,34 @@ def test_whole_layer_chained(case):
     torch.cuda.synchronize()
     for a, t in zip(snap, (L.perm, L.offsets, L.out, L.score)):
         assert np.array_equal(a, to_host(t))
+
+
+def test_fused_forward_matches_the_separate_calls(case):
+    """smoe_forward against the five separate calls on the same device inputs:
+    every output bit for bit (and therefore against the oracle as well)."""
+    c, L, r = case, case.L, case.ref
+    if c.cfg.dtype != wl.BF16:
+        from paper_2308_15030_amd import binding as b
+        with pytest.raises(b.SmoeError):
+            L.forward_fused(c.d_x, c.T, accumulate=0)
+        return
+    res = to_dev(c.x)
+    names = ("orig_expert", "orig_gate", "slot", "gate", "xnorm", "count", "gsum", "score", "perm",
+             "inv_perm", "offsets", "out")
+    L.forward(c.d_x, c.T, accumulate=0, residual=res)
+    L.forward(c.d_x, c.T, accumulate=1, residual=res)
+    torch.cuda.synchronize()
+    want = {n: to_host(getattr(L, n)).copy() for n in names}
+    for n in names:
+        getattr(L, n).fill_(0)
+    L.forward_fused(c.d_x, c.T, accumulate=0, residual=res)
+    L.forward_fused(c.d_x, c.T, accumulate=1, residual=res)
+    torch.cuda.synchronize()
+    for n in names:
+        assert np.array_equal(to_host(getattr(L, n)), want[n]), n
+    # and without a residual, against the oracle directly
+    out = L.forward_fused(c.d_x, c.T, accumulate=0)
+    torch.cuda.synchronize()
+    ok = ~r["ambiguous"]
+    err = max_abs_rel(values(to_host(out), c.cfg.dtype)[ok], values(r["out"], c.cfg.dtype)[ok])
+    assert err <= TOL_OUT[c.cfg.dtype]
