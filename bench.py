@@ -78,6 +78,8 @@ def main():
     ap.add_argument("--decode-layers", type=int, default=1,
                     help="c4 only: independent layers per decode step (6 exceeds the 256 MB Infinity Cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="drive the layer through the five per-step calls instead of smoe_forward")
     ap.add_argument("--no-events", action="store_true",
                     help="do not record per-kernel events inside the timed region")
     args = ap.parse_args()
@@ -112,6 +114,9 @@ def main():
             host0 = host
     print(f"[bench] {cfg.name}: {L} layer(s) set up in {time.time() - t_setup:.1f}s", file=sys.stderr, flush=True)
 
+    def fwd(lay):
+        return lay.forward if args.separate_calls else lay.forward_fused
+
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps * L)] if use_events else []
     active_log = []
 
@@ -124,7 +129,7 @@ def main():
             for l, lay in enumerate(layers):
                 if k is not None and use_events:
                     b.smoe_set_profile_events(lay.handle, *evs[k * L + l])
-                x = lay.forward(x, T, accumulate=1, residual=x)      # residual stream: next layer reads x + MoE(x)
+                x = fwd(lay)(x, T, accumulate=1, residual=x)         # residual stream: next layer reads x + MoE(x)
             return x
 
         for _ in range(warmup):
@@ -155,7 +160,7 @@ def main():
                 for l, lay in enumerate(layers):
                     if timed and use_events:
                         b.smoe_set_profile_events(lay.handle, *evs[i * L + l])
-                    x = lay.forward(x, T, accumulate=0 if sidx % cfg.period == 0 else 1, residual=x)
+                    x = fwd(lay)(x, T, accumulate=0 if sidx % cfg.period == 0 else 1, residual=x)
                     if log_active:
                         off = lay.offsets.cpu().numpy()
                         active_log.append(int((np.diff(off) > 0).sum()))
@@ -233,6 +238,7 @@ def main():
 
     config = {"workload": cfg.name, "E": cfg.E, "K": cfg.K, "d_model": cfg.d_model, "d_ff": cfg.d_ff,
               "tokens": T, "layers": L,
+              "entry": "five separate calls" if args.separate_calls else "smoe_forward (fused, 4 launches)",
               "step": "route+importance+permute+expert_ffn+combine over all layers"}
     if decode:
         config.update(update_period=cfg.period, experts_swapped=swaps,

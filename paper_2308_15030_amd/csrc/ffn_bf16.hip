@@ -508,12 +508,12 @@ void launch_gemm(const uint16_t* X, const void* Wp, const int32_t* offsets, int 
                            (const uint4*)Wp, offsets, nslots, T, Y, R, N, fz);
 }
 
-constexpr int N_VARIANTS = 7;
+constexpr int N_VARIANTS = 8;
 
 template <bool FIRST>
 void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* offsets, int nslots,
                     uint16_t* Y, int R, int N, int T, const FuseArgs& fz, hipStream_t s) {
-    if (R % 64 != 0 && v < 5) {   // d_model / d_ff are multiples of 32 by contract: 32-deep slices always fit
+    if (R % 64 != 0 && v != 5 && v != 6) {   // d_model / d_ff are multiples of 32 by contract: 32-deep slices always fit
         launch_gemm<1, 4, 4, 32, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s);
         return;
     }
@@ -523,6 +523,7 @@ void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* off
         case 2: launch_gemm<2, 2, 4, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  //  64 x 256
         case 3: launch_gemm<1, 2, 4, 64, 1, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  //  64 x 128
         case 4: launch_gemm<1, 1, 4, 64, 3, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  //  32 x 128
+        case 7: launch_gemm<2, 4, 4, 64, 3, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  // 128 x 256, one wave per SIMD
         case 5: launch_small<1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;   // 32 x 128, streaming
         default: launch_small<4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  // 32 x 32, reduction split 4 ways
     }
