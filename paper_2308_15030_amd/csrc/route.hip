@@ -368,11 +368,17 @@ int launch_mfma(const smoe_layer* L, const void* x, int T, int32_t* oe, float* o
     constexpr int NWR = NEB <= 2 ? 8 : 4;
     size_t lds = (size_t)(NWR * EP * RTP + 2 * NWR * RT) * 4;
     auto kern = route_mfma_kernel<NEB, NWR>;
-    if (lds > 48 * 1024) {
-        int rc = smoe_check_hip(hipFuncSetAttribute((const void*)kern,
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
-                                "smoe_route: LDS size");
-        if (rc) return rc;
+    if (lds > 48 * 1024) {   // raise the kernel's dynamic-LDS limit once per device, not on every launch
+        static int raised_on = -1;
+        int dev_now = 0;
+        (void)hipGetDevice(&dev_now);
+        if (raised_on != dev_now) {
+            int rc = smoe_check_hip(hipFuncSetAttribute((const void*)kern,
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
+                                    "smoe_route: LDS size");
+            if (rc) return rc;
+            raised_on = dev_now;
+        }
     }
     hipLaunchKernelGGL(kern, dim3((T + RT - 1) / RT), dim3(NWR * 64), lds, s, (const uint16_t*)x,
                        (const uint4*)L->d_router_split, L->d_expert_to_slot, T, L->cfg.d_model, L->cfg.E,
@@ -388,11 +394,17 @@ int launch(const smoe_layer* L, const void* x, int T, int32_t* oe, float* og, in
     size_t lds_epi = (size_t)(TB * LDW + TB * (ER + 1)) * 4;
     size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
     auto kern = route_kernel<XT, NEC>;
-    if (lds > 48 * 1024) {
-        int rc = smoe_check_hip(hipFuncSetAttribute((const void*)kern,
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
-                                "smoe_route: LDS size");
-        if (rc) return rc;
+    if (lds > 48 * 1024) {   // raise the kernel's dynamic-LDS limit once per device, not on every launch
+        static int raised_on = -1;
+        int dev_now = 0;
+        (void)hipGetDevice(&dev_now);
+        if (raised_on != dev_now) {
+            int rc = smoe_check_hip(hipFuncSetAttribute((const void*)kern,
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
+                                    "smoe_route: LDS size");
+            if (rc) return rc;
+            raised_on = dev_now;
+        }
     }
     dim3 grid((T + TB - 1) / TB);
     hipLaunchKernelGGL(kern, grid, dim3(THREADS), lds, s, (const XT*)x, L->router_w,
