@@ -14,7 +14,7 @@
 // own feature blocks straight from HBM into registers with contiguous 1-KiB
 // loads, prefetched PD reduction slices ahead in a register ring -- they never
 // touch LDS, since no other wave of the workgroup needs them.  The token tile
-// is what the waves share; it is staged through a double-buffered LDS tile.
+// is what the waves share; it is staged through a three-stage LDS ring.
 //
 // The hidden activations h never leave the library, so they are kept in
 // fragment order too: rows are re-based per segment to a multiple of 32
@@ -25,8 +25,10 @@
 //
 // Workgroup = NW waves; tile = (32*MAXB tokens) x (NW*AF*32 features); wave w
 // owns AF feature blocks and all token blocks: AF*NBF accumulators of 16 VGPRs.
-// Token tiles are enumerated per slot from the device-side offsets.
+// Token tiles are enumerated per slot from the device-side offsets; the tiled
+// kernel runs as persistent workgroups that each walk a fixed share of the tiles.
 
+#include <algorithm>
 #include <cstdlib>
 #include <type_traits>
 
@@ -114,6 +116,74 @@ __device__ __forceinline__ bool find_item(const int32_t* __restrict__ offsets, i
         pad_before += __shfl(pin, 63);
     }
     return false;
+}
+
+// ---------------------------------------------------------------------------
+// Persistent form of the enumeration, for the tiled kernel.  The work items
+// (row tile mt, feature tile ft) are numbered g = mt * ftiles + ft, and die x
+// owns the x-th eighth of that list: the dies' shares differ by at most one
+// item (a split by whole row tiles can leave one die with a fifth more work and
+// a whole extra round of tiles), a share still covers few slots, and on a die
+// the feature tile varies fastest, so the workgroups that run together stream
+// many different weight tiles at once (more bytes in flight to HBM) while they
+// share the die's few token tiles through its L2.  The grid holds as many
+// workgroups as the chip keeps resident; the j-th workgroup of a die takes the
+// die's items j, j + n, j + 2n, ... (n workgroups per die).  Each workgroup
+// builds the per-slot tables once, in LDS.
+constexpr int MAX_SLOTS = 256;            // K <= E <= 256 by the C ABI
+
+struct ItemMap {
+    int first[MAX_SLOTS + 1];             // row tiles before slot k; [nslots] = all row tiles
+    int pad[MAX_SLOTS];                   // padded rows (segments re-based to multiples of 32) before slot k
+    int a[MAX_SLOTS], b[MAX_SLOTS];       // clamped segment bounds
+};
+
+// Called by every thread of the workgroup; ends with a barrier.
+__device__ __forceinline__ void build_item_map(ItemMap& m, const int32_t* __restrict__ offsets, int nslots,
+                                               int T, int bt) {
+    if (threadIdx.x < 64) {
+        const int lane = threadIdx.x;
+        int tiles_before = 0, pad_before = 0;
+        for (int base = 0; base < nslots; base += 64) {
+            const int k = base + lane;
+            int a = 0, b = 0, tiles = 0, pad = 0;
+            if (k < nslots) {
+                a = min(max(offsets[k], 0), T);                 // clamps guard misuse
+                b = max(min(max(offsets[k + 1], 0), T), a);
+                tiles = (b - a + bt - 1) / bt;
+                pad = (b - a + 31) & ~31;
+            }
+            const int tin = wave_incl_scan(tiles, lane), pin = wave_incl_scan(pad, lane);
+            if (k < nslots) {
+                m.first[k] = tiles_before + tin - tiles;
+                m.pad[k] = pad_before + pin - pad;
+                m.a[k] = a;
+                m.b[k] = b;
+            }
+            tiles_before += __shfl(tin, 63);
+            pad_before += __shfl(pin, 63);
+        }
+        if (lane == 0) m.first[nslots] = tiles_before;
+    }
+    __syncthreads();
+}
+
+// Row tile mt of the global list: its slot, first row, segment end and padded
+// first row.  Every wave works this out for itself; the results are scalars.
+__device__ __forceinline__ void row_tile_at(const ItemMap& m, int nslots, int bt, int mt, int& slot, int& m0,
+                                            int& m_end, int& pm0) {
+    const int lane = threadIdx.x & 63;
+    int nle = 0;                                               // slots whose first row tile is <= mt
+    for (int base = 0; base < nslots; base += 64) {
+        const int k = base + lane;
+        nle += __popcll(__ballot(k < nslots && m.first[k] <= mt));
+    }
+    const int k = __builtin_amdgcn_readfirstlane(nle - 1);     // the last of them holds mt (empty slots repeat the next first)
+    const int within = mt - __builtin_amdgcn_readfirstlane(m.first[k]);
+    slot = k;
+    m0 = __builtin_amdgcn_readfirstlane(m.a[k]) + within * bt;
+    m_end = __builtin_amdgcn_readfirstlane(m.b[k]);
+    pm0 = __builtin_amdgcn_readfirstlane(m.pad[k]) + within * bt;
 }
 
 __device__ __forceinline__ bf16x8 as_frag(uint4 v) {
@@ -211,17 +281,30 @@ __device__ __forceinline__ void run_tile(const uint16_t* __restrict__ X, const u
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-    // Software pipeline.  Weights: a ring of PD+1 slices in registers, loaded PD
-    // slices ahead; tokens: two register sets, loaded TWO slices ahead and
-    // copied into the LDS double buffer one slice ahead, so every global load
-    // has at least a full slice of MFMA work to land; operands: the next
-    // reduction step's LDS reads are issued before the current step's MFMAs.
-    // Loads past the last slice are clamped to it (fetched again, never used)
-    // so the loop body has no conditional loads.  With PD = 0 (odd slice
-    // counts) the token distance drops to one slice.
-    constexpr int TD = (PD & 1) ? 2 : 1;
+    // Software pipeline over the reduction slices c = 0 .. nchunks-1.
+    //   weights: a ring of PD+1 slices in registers, loaded PD slices ahead;
+    //   tokens:  TD register sets, loaded TD+1 slices ahead, written to LDS one
+    //            slice ahead; LDS holds three stages (slice c in stage c % 3);
+    //   operands: the next MFMA step's LDS reads are issued before the current
+    //            step's MFMAs, across the slice boundary as well.
+    // The one barrier per slice sits in the MIDDLE of the slice's MFMA steps: it
+    // publishes stage (c+1)%3, written at the top of slice c, before the first
+    // read of it at the bottom of slice c, and it orders the last reads of slice
+    // c-1 (all issued before it) ahead of the writes that recycle that stage at
+    // the top of slice c+1.  So no wave ever waits at a barrier with an empty
+    // matrix pipe behind it.
+    // Loads past the last slice are clamped to it (fetched again, never used),
+    // so the loop body has no conditional loads.
+    // With more than 4 token blocks the operand reads are pipelined in two
+    // half-steps of the block range, which halves the operand registers.
+    constexpr int TD = ((PD & 1) && AF * NBF < 16) ? 2 : 1;   // the largest tile keeps one set only
+    constexpr int NG = NBF > 4 ? 2 : 1;                   // operand groups per reduction step
+    constexpr int GB = (NBF + NG - 1) / NG;               // token blocks per group
+    constexpr int NSTEP = KS * NG;
+    static_assert(KS % 2 == 0, "the operand double buffer assumes an even number of steps per slice");
     uint4 tregA[CPT], tregB[CPT];                       // token register sets 0 and 1
     uint4 wbuf[PD + 1][KS][AF];
+    bf16x8 xf[2][GB];
 #pragma unroll
     for (int i = 0; i < CPT; ++i) tregA[i] = *(const uint4*)tsrc[i];
 #pragma unroll
@@ -239,54 +322,66 @@ __device__ __forceinline__ void run_tile(const uint16_t* __restrict__ X, const u
     }
 #pragma unroll
     for (int i = 0; i < CPT; ++i) *(uint4*)&xs[tdst[i]] = tregA[i];
+    {   // set 0 is free again: it takes slice TD (the slice after the ones already loaded)
+        const int c2 = min(TD, nchunks - 1);
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) tregA[i] = *(const uint4*)(tsrc[i] + (size_t)c2 * tstep);
+    }
     __syncthreads();
+#pragma unroll
+    for (int b = 0; b < GB; ++b) xf[0][b] = as_frag(*(const uint4*)&xs[xoff + b * XB]);
 
+    int st = 0;                                           // LDS stage of the current slice
     // nchunks is a multiple of PD+1 (the launcher picks PD so; PD is 0, 1 or 3),
     // and every ring index below is a compile-time constant.
     auto slice = [&](auto uc, int c0) {
         constexpr int u = decltype(uc)::value;            // position in the ring: compile-time
         const int c = c0 + u;
-        const int cw = min(c + PD, nchunks - 1), ct = min(c + TD, nchunks - 1);
-        const uint16_t* tile = xs + (c & 1) * stage_elems + xoff;
-        bf16x8 xf[2][NBF];
-#pragma unroll
-        for (int b = 0; b < NBF; ++b) xf[0][b] = as_frag(*(const uint4*)&tile[b * XB]);
+        const int cw = min(c + PD, nchunks - 1), ct = min(c + TD + 1, nchunks - 1);
+        const int st1 = st == 2 ? 0 : st + 1;
+        const uint16_t* tile = xs + st * stage_elems + xoff;
+        const uint16_t* tile1 = xs + st1 * stage_elems + xoff;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int a = 0; a < AF; ++a)
                 wbuf[(u + PD) % (PD + 1)][ks][a] = wbase[a][(size_t)(cw * KS + ks) * 64];
-        // set u%TD held slice c (already in LDS); it now receives slice c+TD
-#pragma unroll
-        for (int i = 0; i < CPT; ++i) {
-            uint4 v = *(const uint4*)(tsrc[i] + (size_t)ct * tstep);
-            if constexpr (u % TD == 0) tregA[i] = v; else tregB[i] = v;
-        }
-        __builtin_amdgcn_sched_barrier(0);                // keep the prefetches ahead of the math
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            if (ks + 1 < KS) {
-#pragma unroll
-                for (int b = 0; b < NBF; ++b)
-                    xf[(ks + 1) & 1][b] = as_frag(*(const uint4*)&tile[b * XB + (ks + 1) * XK]);
-            }
-            __builtin_amdgcn_sched_barrier(0);            // next step's operands are on their way
-#pragma unroll
-            for (int b = 0; b < NBF; ++b)
-#pragma unroll
-                for (int a = 0; a < AF; ++a)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(wbuf[u][ks][a]), xf[ks & 1][b],
-                                                                        acc[a][b], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        // slice c+1 (register set (u+1)%TD) goes into the other LDS stage
-        uint16_t* dst = xs + ((c + 1) & 1) * stage_elems;
+        // the set that holds slice c+1 goes to stage (c+1)%3 and is reloaded with slice c+TD+1
+        uint16_t* dst = xs + st1 * stage_elems;
 #pragma unroll
         for (int i = 0; i < CPT; ++i) {
             if constexpr ((u + 1) % TD == 0) *(uint4*)&dst[tdst[i]] = tregA[i];
             else *(uint4*)&dst[tdst[i]] = tregB[i];
         }
-        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+            uint4 v = *(const uint4*)(tsrc[i] + (size_t)ct * tstep);
+            if constexpr ((u + 1) % TD == 0) tregA[i] = v; else tregB[i] = v;
+        }
+        __builtin_amdgcn_sched_barrier(0);                // keep the prefetches ahead of the math
+#pragma unroll
+        for (int t = 0; t < NSTEP; ++t) {
+            const int ks = t / NG, g = t % NG;
+            if (t == NSTEP / 2) __syncthreads();          // stage (c+1)%3 is complete from here on
+            {   // operands of step t+1: the next group, the next reduction step, or the next slice
+                const int t1 = t + 1;
+                const int ks1 = (t1 % NSTEP) / NG, g1 = t1 % NG;
+                const uint16_t* src = (t1 == NSTEP ? tile1 : tile) + ks1 * XK;
+#pragma unroll
+                for (int b = 0; b < GB; ++b)
+                    if (g1 * GB + b < NBF) xf[t1 & 1][b] = as_frag(*(const uint4*)&src[(g1 * GB + b) * XB]);
+            }
+            __builtin_amdgcn_sched_barrier(0);            // next step's operands are on their way
+#pragma unroll
+            for (int b = 0; b < GB; ++b)
+#pragma unroll
+                for (int a = 0; a < AF; ++a)
+                    if (g * GB + b < NBF)
+                        acc[a][g * GB + b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            as_frag(wbuf[u][ks][a]), xf[t & 1][b], acc[a][g * GB + b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        st = st1;
     };
     for (int c0 = 0; c0 < nchunks; c0 += PD + 1) {
         slice(std::integral_constant<int, 0>{}, c0);
@@ -296,6 +391,7 @@ __device__ __forceinline__ void run_tile(const uint16_t* __restrict__ X, const u
             slice(std::integral_constant<int, 3>{}, c0);
         }
     }
+    __syncthreads();                                      // the next tile's first write may hit any stage
 
     // accumulator register i of lane l: feature 8*(i/4) + 4*(l/32) + i%4, token l%32
 #pragma unroll
@@ -351,17 +447,29 @@ struct TileSwitch {
 
 // FIRST = the d_model -> d_ff product: row-major x_perm in, ReLU, fragment-order h out.
 // Otherwise the d_ff -> d_model product: fragment-order h in, row-major y_perm out.
+// Persistent workgroups (see the enumeration above).
 template <int AF, int MAXB, int NW, int BKT, int PD, int OCC, bool FIRST>
 __global__ __launch_bounds__(NW * 64, OCC) void grouped_gemm_bf16(
     const uint16_t* __restrict__ X, const uint4* __restrict__ Wp, const int32_t* __restrict__ offsets,
     int nslots, int T, uint16_t* __restrict__ Y, int R, int N, const FuseArgs fz) {
-    __shared__ __align__(16) uint16_t xs[2 * MAXB * 32 * (BKT + KPAD)];
-    int slot, ftile, m0, m_end, pm0;
+    __shared__ __align__(16) uint16_t xs[3 * MAXB * 32 * (BKT + KPAD)];
+    __shared__ ItemMap map;
+    constexpr int BT = MAXB * 32;
     const int ftiles = ((N >> 5) + NW * AF - 1) / (NW * AF);
-    if (!find_item(offsets, nslots, T, MAXB * 32, ftiles, blockIdx.x, slot, ftile, m0, m_end, pm0)) return;
-    const int nbf = min(MAXB, (m_end - m0 + 31) >> 5);    // token blocks that hold real rows
-    TileSwitch<AF, MAXB, MAXB, NW, BKT, PD, !FIRST, FIRST, FIRST>::go(nbf, X, Wp, Y, R, N, slot, m0, m_end, pm0,
-                                                                     ftile, xs, fz);
+    build_item_map(map, offsets, nslots, T, BT);
+    const long long G = (long long)__builtin_amdgcn_readfirstlane(map.first[nslots]) * ftiles;
+    const int die = blockIdx.x % XCDS, nwg = gridDim.x / XCDS;   // the grid is a multiple of 8
+    const long long lo = G * die / XCDS;
+    const int cnt = (int)(G * (die + 1) / XCDS - lo);
+    for (int j = blockIdx.x / XCDS; j < cnt; j += nwg) {
+        const long long g = lo + j;
+        const int mt = (int)(g / ftiles), ftile = (int)(g % ftiles);
+        int slot, m0, m_end, pm0;
+        row_tile_at(map, nslots, BT, mt, slot, m0, m_end, pm0);
+        const int nbf = min(MAXB, (m_end - m0 + 31) >> 5);    // token blocks that hold real rows
+        TileSwitch<AF, MAXB, MAXB, NW, BKT, PD, !FIRST, FIRST, FIRST>::go(nbf, X, Wp, Y, R, N, slot, m0, m_end,
+                                                                         pm0, ftile, xs, fz);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -492,14 +600,30 @@ void launch_small(const uint16_t* X, const void* Wp, const int32_t* offsets, int
                        nslots, T, Y, R, N, fz);
 }
 
+// Compute units per die, asked of the runtime once.
+int cus_per_die() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0, cus = 0;
+        (void)hipGetDevice(&dev);
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < XCDS)
+            cus = 256;
+        n = cus / XCDS;
+    }
+    return n;
+}
+
 template <int AF, int MAXB, int NW, int BKT, int PD, int OCC, bool FIRST>
 void launch_gemm(const uint16_t* X, const void* Wp, const int32_t* offsets, int nslots, uint16_t* Y,
                  int R, int N, int T, const FuseArgs& fz, hipStream_t s) {
     constexpr int BT = 32 * MAXB;
-    int mtiles = (T + BT - 1) / BT + nslots;               // upper bound on the row tiles of all slots
-    int ftiles = ((N >> 5) + NW * AF - 1) / (NW * AF);
-    // a die gets at most ceil(mtiles / 8) row tiles, each with all feature tiles; surplus workgroups exit
-    dim3 grid(XCDS * ((mtiles + XCDS - 1) / XCDS) * ftiles);
+    const int mtiles = (T + BT - 1) / BT + nslots;         // upper bound on the row tiles of all slots
+    const int ftiles = ((N >> 5) + NW * AF - 1) / (NW * AF);
+    const long long items = (long long)mtiles * ftiles;
+    // as many workgroups as the chip holds at once (OCC waves per SIMD), or fewer if the items run out
+    const int resident = cus_per_die() * std::max(1, OCC * 4 / NW);
+    const int per_die = (int)std::min<long long>((items + XCDS - 1) / XCDS, resident);
+    dim3 grid(XCDS * std::max(per_die, 1));
     if ((R / BKT) % (PD + 1) == 0)
         hipLaunchKernelGGL((grouped_gemm_bf16<AF, MAXB, NW, BKT, PD, OCC, FIRST>), grid, dim3(NW * 64), 0, s, X,
                            (const uint4*)Wp, offsets, nslots, T, Y, R, N, fz);
@@ -508,12 +632,12 @@ void launch_gemm(const uint16_t* X, const void* Wp, const int32_t* offsets, int 
                            (const uint4*)Wp, offsets, nslots, T, Y, R, N, fz);
 }
 
-constexpr int N_VARIANTS = 8;
+constexpr int N_VARIANTS = 14;
 
 template <bool FIRST>
 void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* offsets, int nslots,
                     uint16_t* Y, int R, int N, int T, const FuseArgs& fz, hipStream_t s) {
-    if (R % 64 != 0 && v != 5 && v != 6) {   // d_model / d_ff are multiples of 32 by contract: 32-deep slices always fit
+    if ((R % 64 != 0 || (v >= 12 && R % 128 != 0)) && v != 5 && v != 6) {   // d_model / d_ff are multiples of 32 by contract: 32-deep slices always fit
         launch_gemm<1, 4, 4, 32, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s);
         return;
     }
@@ -524,6 +648,12 @@ void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* off
         case 3: launch_gemm<1, 2, 4, 64, 1, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  //  64 x 128
         case 4: launch_gemm<1, 1, 4, 64, 3, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  //  32 x 128
         case 7: launch_gemm<2, 4, 4, 64, 3, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  // 128 x 256, one wave per SIMD
+        case 8: launch_gemm<1, 4, 8, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  // 128 x 256, 8 waves
+        case 9: launch_gemm<1, 4, 4, 64, 3, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  // 128 x 128, deep prefetch
+        case 10: launch_gemm<1, 2, 4, 64, 3, 3, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break; //  64 x 128, deep prefetch
+        case 11: launch_gemm<2, 2, 4, 64, 3, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break; //  64 x 256, deep prefetch
+        case 12: launch_gemm<1, 4, 8, 128, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break; // 128 x 256, 8 waves, 128-deep slices
+        case 13: launch_gemm<2, 4, 4, 128, 1, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break; // 128 x 256, 128-deep slices
         case 5: launch_small<1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;   // 32 x 128, streaming
         default: launch_small<4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  // 32 x 32, reduction split 4 ways
     }
@@ -533,7 +663,7 @@ void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* off
 // built-in choice (a tuning aid; the indices are those of launch_variant).
 void pick_variants(const smoe_config& c, int T, int& v1, int& v2) {
     int per_slot = T / c.K;
-    if (per_slot >= 96) { v1 = 1; v2 = 1; }
+    if (per_slot >= 96) { v1 = 8; v2 = 1; }
     else if (per_slot >= 48) { v1 = 2; v2 = 3; }
     else if (per_slot >= 8) { v1 = 4; v2 = 4; }
     else { v1 = 5; v2 = 6; }             // decode: a few tokens per slot, weight streaming
