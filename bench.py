@@ -39,9 +39,9 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0      # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per grouped-GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on
-# the default command (profiles/c3_prefill_hbm_counters.txt), mean of the two
+# the default command (profiles/grouped_gemm_bf16_c3_prefill_hbm_counters.txt), mean of the two
 # launches of one FFN; None for any other configuration.
-MEASURED_TRAFFIC_C3 = 132.5e6
+MEASURED_TRAFFIC_C3 = 143.8e6
 
 
 def dev_t(a, dev):
@@ -117,12 +117,13 @@ def main():
     def fwd(lay):
         return lay.forward if args.separate_calls else lay.forward_fused
 
-    # Per-kernel events bracket the two grouped-GEMM launches of ONE layer call per
-    # sampled step (layer k % L at step k; decode samples every 4th step): three event
-    # records cost about as much as a small kernel, so bracketing every call would
-    # slow the very region whose throughput is being measured.
+    # Per-kernel events ride on the two grouped-GEMM dispatches of ONE layer call per
+    # sampled step (layer k % L at step k; decode samples every 4th step): each pair
+    # reads the start and end of that kernel's execution.  Timed dispatches carry a
+    # completion signal each, so attaching events to every call would slow the very
+    # region whose throughput is being measured.
     ev_stride = 4 if decode else 1
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)] if use_events else []
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)] if use_events else []
     ev_used = []
     active_log = []
 
@@ -197,7 +198,7 @@ def main():
     roof = None
     if use_events:
         g1 = np.array([evs[i][0].elapsed_time(evs[i][1]) for i in ev_used]) * 1e-3
-        g2 = np.array([evs[i][1].elapsed_time(evs[i][2]) for i in ev_used]) * 1e-3
+        g2 = np.array([evs[i][2].elapsed_time(evs[i][3]) for i in ev_used]) * 1e-3
         avg = (g1.mean() + g2.mean()) / 2.0                    # mean duration of one grouped-GEMM launch
         if not decode:
             flops = 2.0 * T * cfg.d_model * cfg.d_ff           # per launch; two launches per FFN

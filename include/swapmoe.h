@@ -188,13 +188,15 @@ int smoe_forward(smoe_layer_t* layer, const void* x, int T, const void* residual
                  float* xnorm, int32_t* count, float* gsum, float* score, int32_t* perm,
                  int32_t* inv_perm, int32_t* offsets, void* stream);
 
-/* Measurement aid (not part of the paper's method): HIP events the NEXT
- * smoe_expert_ffn (or smoe_forward) call on this handle records on its stream -- ev_begin before
- * the first product, ev_mid between the two products, ev_end after the second
- * -- so each kernel's duration can be read with hipEventElapsedTime.  The
- * events are caller-owned hipEvent_t values passed as void*; they are used
- * once and then forgotten.  Pass three NULLs to cancel. */
-int smoe_set_profile_events(smoe_layer_t* layer, void* ev_begin, void* ev_mid, void* ev_end);
+/* Measurement aid (not part of the paper's method): HIP events for the NEXT
+ * smoe_expert_ffn (or smoe_forward) call on this handle.  The call attaches
+ * them to its two product kernels' own dispatches: g1_begin / g1_end take the
+ * start and end of the first product's execution, g2_begin / g2_end those of
+ * the second, so hipEventElapsedTime(g1_begin, g1_end) is that kernel's
+ * duration with no launch gap in it.  The events are caller-owned hipEvent_t
+ * values passed as void*; they are used once and then forgotten.  Pass four
+ * NULLs to cancel. */
+int smoe_set_profile_events(smoe_layer_t* layer, void* g1_begin, void* g1_end, void* g2_begin, void* g2_end);
 
 /* Gate-weighted combine, y = G(x)_i E_i(x) in token order:
  *   out[t, :] = gate[t] * y_perm[inv_perm[t], :]  (+ residual[t, :] if not NULL)

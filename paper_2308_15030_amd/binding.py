@@ -52,7 +52,7 @@ _SIGS = {
     "smoe_permute": (C.c_int, [_vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp]),
     "smoe_expert_ffn": (C.c_int, [_vp, _vp, _vp, _i, _vp, _vp]),
     "smoe_combine": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _i, _vp, _vp]),
-    "smoe_set_profile_events": (C.c_int, [_vp, _vp, _vp, _vp]),
+    "smoe_set_profile_events": (C.c_int, [_vp, _vp, _vp, _vp, _vp]),
     "smoe_forward": (C.c_int, [_vp, _vp, _i, _vp, _vp, _i] + [_vp] * 12),
 }
 EXPORTS = tuple(_SIGS)
@@ -162,7 +162,7 @@ def smoe_forward(layer, x, T, residual, out, accumulate, orig_expert, orig_gate,
                              _ptr(score), _ptr(perm), _ptr(inv_perm), _ptr(offsets), _stream(stream)))
 
 
-def smoe_set_profile_events(layer, ev_begin, ev_mid, ev_end):
+def smoe_set_profile_events(layer, g1_begin, g1_end, g2_begin, g2_end):
     """Events are torch.cuda.Event(enable_timing=True) objects (or None)."""
     def h(e):
         if e is None:
@@ -170,7 +170,7 @@ def smoe_set_profile_events(layer, ev_begin, ev_mid, ev_end):
         if e.cuda_event == 0:      # torch creates the HIP event lazily, on first record
             e.record()
         return e.cuda_event
-    _check(_lib.smoe_set_profile_events(layer, h(ev_begin), h(ev_mid), h(ev_end)))
+    _check(_lib.smoe_set_profile_events(layer, h(g1_begin), h(g1_end), h(g2_begin), h(g2_end)))
 
 
 # ---------------------------------------------------------------------------

@@ -280,7 +280,7 @@ int smoe_expert_ffn(smoe_layer_t* L, const void* x_perm, const int32_t* offsets,
         rc = smoe_launch_ffn_f32(L, (const float*)x_perm, offsets, T, (float*)y_perm, as_stream(stream));
     else
         rc = smoe_launch_ffn_bf16(L, (const uint16_t*)x_perm, offsets, T, (uint16_t*)y_perm, as_stream(stream));
-    L->prof_ev[0] = L->prof_ev[1] = L->prof_ev[2] = nullptr;
+    L->prof_ev[0] = L->prof_ev[1] = L->prof_ev[2] = L->prof_ev[3] = nullptr;
     return rc;
 }
 
@@ -314,17 +314,18 @@ int smoe_forward(smoe_layer_t* L, const void* x, int T, const void* residual, vo
     if (rc) return rc;
     rc = smoe_launch_ffn_bf16_fused(L, (const uint16_t*)x, perm, offsets, gate, (const uint16_t*)residual, T,
                                     (uint16_t*)out, s);
-    L->prof_ev[0] = L->prof_ev[1] = L->prof_ev[2] = nullptr;
+    L->prof_ev[0] = L->prof_ev[1] = L->prof_ev[2] = L->prof_ev[3] = nullptr;
     return rc;
 }
 
-int smoe_set_profile_events(smoe_layer_t* L, void* ev_begin, void* ev_mid, void* ev_end) {
+int smoe_set_profile_events(smoe_layer_t* L, void* g1_begin, void* g1_end, void* g2_begin, void* g2_end) {
     if (!L) return smoe_fail(SMOE_EINVAL, "smoe_set_profile_events: null handle");
-    bool none = !ev_begin && !ev_mid && !ev_end, all = ev_begin && ev_mid && ev_end;
-    if (!none && !all) return smoe_fail(SMOE_EINVAL, "smoe_set_profile_events: pass three events or three NULLs");
-    L->prof_ev[0] = (hipEvent_t)ev_begin;
-    L->prof_ev[1] = (hipEvent_t)ev_mid;
-    L->prof_ev[2] = (hipEvent_t)ev_end;
+    bool none = !g1_begin && !g1_end && !g2_begin && !g2_end, all = g1_begin && g1_end && g2_begin && g2_end;
+    if (!none && !all) return smoe_fail(SMOE_EINVAL, "smoe_set_profile_events: pass four events or four NULLs");
+    L->prof_ev[0] = (hipEvent_t)g1_begin;
+    L->prof_ev[1] = (hipEvent_t)g1_end;
+    L->prof_ev[2] = (hipEvent_t)g2_begin;
+    L->prof_ev[3] = (hipEvent_t)g2_end;
     return SMOE_OK;
 }
 

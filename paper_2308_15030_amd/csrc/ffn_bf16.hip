@@ -591,13 +591,13 @@ __global__ __launch_bounds__(256) void small_gemm_bf16(
 
 template <int KSPLIT, bool FIRST>
 void launch_small(const uint16_t* X, const void* Wp, const int32_t* offsets, int nslots, uint16_t* Y, int R,
-                  int N, int T, const FuseArgs& fz, hipStream_t s) {
+                  int N, int T, const FuseArgs& fz, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
     int mtiles = (T + 31) / 32 + nslots;
     int nfb = N >> 5;
     int ftiles = KSPLIT == 1 ? (nfb + 3) / 4 : nfb;
     dim3 grid(XCDS * ((mtiles + XCDS - 1) / XCDS) * ftiles);
-    hipLaunchKernelGGL((small_gemm_bf16<KSPLIT, FIRST>), grid, dim3(256), 0, s, X, (const uint4*)Wp, offsets,
-                       nslots, T, Y, R, N, fz);
+    smoe_launch_timed(small_gemm_bf16<KSPLIT, FIRST>, grid, dim3(256), s, e0, e1, X, (const uint4*)Wp, offsets,
+                      nslots, T, Y, R, N, fz);
 }
 
 // Compute units per die, asked of the runtime once.
@@ -615,7 +615,7 @@ int cus_per_die() {
 
 template <int AF, int MAXB, int NW, int BKT, int PD, int OCC, bool FIRST>
 void launch_gemm(const uint16_t* X, const void* Wp, const int32_t* offsets, int nslots, uint16_t* Y,
-                 int R, int N, int T, const FuseArgs& fz, hipStream_t s) {
+                 int R, int N, int T, const FuseArgs& fz, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
     constexpr int BT = 32 * MAXB;
     const int mtiles = (T + BT - 1) / BT + nslots;         // upper bound on the row tiles of all slots
     const int ftiles = ((N >> 5) + NW * AF - 1) / (NW * AF);
@@ -625,37 +625,33 @@ void launch_gemm(const uint16_t* X, const void* Wp, const int32_t* offsets, int 
     const int per_die = (int)std::min<long long>((items + XCDS - 1) / XCDS, resident);
     dim3 grid(XCDS * std::max(per_die, 1));
     if ((R / BKT) % (PD + 1) == 0)
-        hipLaunchKernelGGL((grouped_gemm_bf16<AF, MAXB, NW, BKT, PD, OCC, FIRST>), grid, dim3(NW * 64), 0, s, X,
-                           (const uint4*)Wp, offsets, nslots, T, Y, R, N, fz);
+        smoe_launch_timed(grouped_gemm_bf16<AF, MAXB, NW, BKT, PD, OCC, FIRST>, grid, dim3(NW * 64), s, e0, e1, X,
+                          (const uint4*)Wp, offsets, nslots, T, Y, R, N, fz);
     else   // slice count not a multiple of the ring length: same tile without weight prefetch
-        hipLaunchKernelGGL((grouped_gemm_bf16<AF, MAXB, NW, BKT, 0, OCC, FIRST>), grid, dim3(NW * 64), 0, s, X,
-                           (const uint4*)Wp, offsets, nslots, T, Y, R, N, fz);
+        smoe_launch_timed(grouped_gemm_bf16<AF, MAXB, NW, BKT, 0, OCC, FIRST>, grid, dim3(NW * 64), s, e0, e1, X,
+                          (const uint4*)Wp, offsets, nslots, T, Y, R, N, fz);
 }
 
-constexpr int N_VARIANTS = 14;
+constexpr int N_VARIANTS = 9;
 
 template <bool FIRST>
 void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* offsets, int nslots,
-                    uint16_t* Y, int R, int N, int T, const FuseArgs& fz, hipStream_t s) {
-    if ((R % 64 != 0 || (v >= 12 && R % 128 != 0)) && v != 5 && v != 6) {   // d_model / d_ff are multiples of 32 by contract: 32-deep slices always fit
-        launch_gemm<1, 4, 4, 32, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s);
+                    uint16_t* Y, int R, int N, int T, const FuseArgs& fz, hipStream_t s, hipEvent_t e0,
+                    hipEvent_t e1) {
+    if (R % 64 != 0 && v != 5 && v != 6) {   // d_model / d_ff are multiples of 32 by contract: 32-deep slices always fit
+        launch_gemm<1, 4, 4, 32, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1);
         return;
     }
     switch (v) {             //            AF MAXB NW BKT PD OCC     tokens x features per workgroup
-        case 0: launch_gemm<2, 8, 4, 64, 1, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  // 256 x 256
-        case 1: launch_gemm<1, 4, 4, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  // 128 x 128
-        case 2: launch_gemm<2, 2, 4, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  //  64 x 256
-        case 3: launch_gemm<1, 2, 4, 64, 1, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  //  64 x 128
-        case 4: launch_gemm<1, 1, 4, 64, 3, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  //  32 x 128
-        case 7: launch_gemm<2, 4, 4, 64, 3, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  // 128 x 256, one wave per SIMD
-        case 8: launch_gemm<1, 4, 8, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  // 128 x 256, 8 waves
-        case 9: launch_gemm<1, 4, 4, 64, 3, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  // 128 x 128, deep prefetch
-        case 10: launch_gemm<1, 2, 4, 64, 3, 3, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break; //  64 x 128, deep prefetch
-        case 11: launch_gemm<2, 2, 4, 64, 3, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break; //  64 x 256, deep prefetch
-        case 12: launch_gemm<1, 4, 8, 128, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break; // 128 x 256, 8 waves, 128-deep slices
-        case 13: launch_gemm<2, 4, 4, 128, 1, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break; // 128 x 256, 128-deep slices
-        case 5: launch_small<1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;   // 32 x 128, streaming
-        default: launch_small<4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s); break;  // 32 x 32, reduction split 4 ways
+        case 0: launch_gemm<2, 8, 4, 64, 1, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  // 256 x 256
+        case 1: launch_gemm<1, 4, 4, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  // 128 x 128
+        case 2: launch_gemm<2, 2, 4, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  //  64 x 256
+        case 3: launch_gemm<1, 2, 4, 64, 1, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  //  64 x 128
+        case 4: launch_gemm<1, 1, 4, 64, 3, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  //  32 x 128
+        case 7: launch_gemm<2, 4, 4, 64, 3, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  // 128 x 256, one wave per SIMD
+        case 8: launch_gemm<1, 4, 8, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  // 128 x 256, 8 waves
+        case 5: launch_small<1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;   // 32 x 128, streaming
+        default: launch_small<4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  // 32 x 32, reduction split 4 ways
     }
 }
 
@@ -686,11 +682,8 @@ int smoe_launch_ffn_bf16(const smoe_layer* L, const uint16_t* x_perm, const int3
     pick_variants(c, T, v1, v2);
     uint16_t* h = (uint16_t*)L->d_hidden;
     const FuseArgs none{nullptr, nullptr, nullptr};
-    if (L->prof_ev[0]) (void)hipEventRecord(L->prof_ev[0], s);
-    launch_variant<true>(v1, x_perm, L->slot_w1, offsets, c.K, h, c.d_model, c.d_ff, T, none, s);
-    if (L->prof_ev[1]) (void)hipEventRecord(L->prof_ev[1], s);
-    launch_variant<false>(v2, h, L->slot_w2, offsets, c.K, y_perm, c.d_ff, c.d_model, T, none, s);
-    if (L->prof_ev[2]) (void)hipEventRecord(L->prof_ev[2], s);
+    launch_variant<true>(v1, x_perm, L->slot_w1, offsets, c.K, h, c.d_model, c.d_ff, T, none, s, L->prof_ev[0], L->prof_ev[1]);
+    launch_variant<false>(v2, h, L->slot_w2, offsets, c.K, y_perm, c.d_ff, c.d_model, T, none, s, L->prof_ev[2], L->prof_ev[3]);
     return smoe_check_hip(hipGetLastError(), "smoe_expert_ffn launch");
 }
 
@@ -704,10 +697,7 @@ int smoe_launch_ffn_bf16_fused(const smoe_layer* L, const uint16_t* x, const int
     pick_variants(c, T, v1, v2);
     uint16_t* h = (uint16_t*)L->d_hidden;
     const FuseArgs gather{perm, nullptr, nullptr}, scatter{perm, gate, residual};
-    if (L->prof_ev[0]) (void)hipEventRecord(L->prof_ev[0], s);
-    launch_variant<true>(v1, x, L->slot_w1, offsets, c.K, h, c.d_model, c.d_ff, T, gather, s);
-    if (L->prof_ev[1]) (void)hipEventRecord(L->prof_ev[1], s);
-    launch_variant<false>(v2, h, L->slot_w2, offsets, c.K, out, c.d_ff, c.d_model, T, scatter, s);
-    if (L->prof_ev[2]) (void)hipEventRecord(L->prof_ev[2], s);
+    launch_variant<true>(v1, x, L->slot_w1, offsets, c.K, h, c.d_model, c.d_ff, T, gather, s, L->prof_ev[0], L->prof_ev[1]);
+    launch_variant<false>(v2, h, L->slot_w2, offsets, c.K, out, c.d_ff, c.d_model, T, scatter, s, L->prof_ev[2], L->prof_ev[3]);
     return smoe_check_hip(hipGetLastError(), "smoe_forward: FFN launch");
 }

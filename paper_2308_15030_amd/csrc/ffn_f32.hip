@@ -85,12 +85,10 @@ int smoe_launch_ffn_f32(const smoe_layer* L, const float* x_perm, const int32_t*
     const smoe_config& c = L->cfg;
     const int mtiles = (T + BM - 1) / BM + c.K;            // upper bound; surplus workgroups exit
     float* h = (float*)L->d_hidden;
-    if (L->prof_ev[0]) (void)hipEventRecord(L->prof_ev[0], s);
-    hipLaunchKernelGGL(grouped_gemm_f32<true>, dim3(mtiles, (c.d_ff + BN - 1) / BN), dim3(256), 0, s,
-                       x_perm, (const float*)L->slot_w1, offsets, c.K, T, h, c.d_model, c.d_ff);
-    if (L->prof_ev[1]) (void)hipEventRecord(L->prof_ev[1], s);
-    hipLaunchKernelGGL(grouped_gemm_f32<false>, dim3(mtiles, (c.d_model + BN - 1) / BN), dim3(256), 0, s,
-                       (const float*)h, (const float*)L->slot_w2, offsets, c.K, T, y_perm, c.d_ff, c.d_model);
-    if (L->prof_ev[2]) (void)hipEventRecord(L->prof_ev[2], s);
+    smoe_launch_timed(grouped_gemm_f32<true>, dim3(mtiles, (c.d_ff + BN - 1) / BN), dim3(256), s, L->prof_ev[0],
+                      L->prof_ev[1], x_perm, (const float*)L->slot_w1, offsets, c.K, T, h, c.d_model, c.d_ff);
+    smoe_launch_timed(grouped_gemm_f32<false>, dim3(mtiles, (c.d_model + BN - 1) / BN), dim3(256), s,
+                      L->prof_ev[2], L->prof_ev[3], (const float*)h, (const float*)L->slot_w2, offsets, c.K, T,
+                      y_perm, c.d_ff, c.d_model);
     return smoe_check_hip(hipGetLastError(), "smoe_expert_ffn launch");
 }

@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stddef.h>
 #include <vector>
@@ -39,7 +40,7 @@ struct smoe_layer {
     void* d_router_split = nullptr;          // bf16 path: router weights split in three, MFMA order
     bool router_split_done = false;          // made by the first smoe_route after a bind
 
-    hipEvent_t prof_ev[3] = {nullptr, nullptr, nullptr};   // one-shot FFN profiling events
+    hipEvent_t prof_ev[4] = {nullptr, nullptr, nullptr, nullptr};   // one-shot FFN profiling events
 };
 
 struct smoe_ws_layout {
@@ -83,6 +84,15 @@ int smoe_launch_expert_norm(const smoe_layer* L, const void* w1, const void* w2,
                             hipStream_t s);
 int smoe_launch_clear_maps(const smoe_layer* L, hipStream_t s);
 int smoe_launch_split_router(const smoe_layer* L, hipStream_t s);
+
+// Kernel launch that, when a pair of events is given, attaches them to the
+// dispatch itself (start and end of the kernel's execution).
+template <typename K, typename... Args>
+inline void smoe_launch_timed(K kernel, dim3 grid, dim3 block, hipStream_t s, hipEvent_t e0, hipEvent_t e1,
+                              Args... args) {
+    if (e0 && e1) hipExtLaunchKernelGGL(kernel, grid, block, 0, s, e0, e1, 0, args...);
+    else hipLaunchKernelGGL(kernel, grid, block, 0, s, args...);
+}
 
 // bf16 <-> fp32 on the device.  Widening is exact; narrowing rounds to
 // nearest, ties to even (inputs are finite by contract).
