@@ -476,128 +476,170 @@ __global__ __launch_bounds__(NW * 64, OCC) void grouped_gemm_bf16(
 // Small-batch (decode) variant: row tiles of 32 tokens, nothing but weight
 // streaming.  With a handful of tokens per slot the FFN is bound by reading
 // each active slot's weights once, so the kernel is built around keeping many
-// 1-KiB weight loads in flight per wave: no LDS staging and no barrier in the
-// loop -- the token operand (32 rows) is read straight from L2 -- and the
-// operands of G reduction steps are fetched together, two groups in flight.
-//   KSPLIT = 1: the workgroup's 4 waves take 4 neighbouring feature blocks;
-//   KSPLIT = 4: they share one feature block and split the reduction four ways,
-//               meeting in LDS at the end (added in wave order: reproducible).
-// The second product (reduction length d_ff, only d_model outputs) uses
-// KSPLIT = 4 so that it, too, spreads over (slots x d_model/32) workgroups.
-template <int KSPLIT, bool FIRST>
-__global__ __launch_bounds__(256) void small_gemm_bf16(
+// 1-KiB weight loads in flight: no LDS staging and no barrier in the loop --
+// the token operand (32 rows) is read straight from L2 -- and the operands of
+// G reduction steps are fetched together, two groups in flight per wave.
+// A workgroup of NWV waves covers NWV / KSPLIT neighbouring feature blocks;
+// the KSPLIT waves that share a feature block split its reduction and meet in
+// LDS at the end (added in wave order: reproducible).  Splitting shortens the
+// stream each wave has to pull through its own queue of loads, which is what
+// bounds a wave's share of the HBM bandwidth.
+// Workgroup b serves (slot b / ftiles, feature tile b % ftiles): it knows its
+// weights before it knows whether the slot has any tokens, so the first group
+// of weight loads is issued ahead of the read of the offsets and the latency of
+// the two overlaps; the workgroup of an empty slot then simply leaves.  A slot
+// with more than 32 tokens (rare at these batch sizes) is worked off 32 rows
+// at a time.
+template <int NWV, int KSPLIT, bool FIRST>
+__global__ __launch_bounds__(NWV * 64) void small_gemm_bf16(
     const uint16_t* __restrict__ X, const uint4* __restrict__ Wp, const int32_t* __restrict__ offsets,
     int nslots, int T, uint16_t* __restrict__ Y, int R, int N, const FuseArgs fz) {
     constexpr int G = 8;                                   // reduction steps fetched together
+    constexpr int FBW = NWV / KSPLIT;                      // feature blocks per workgroup
     constexpr bool XFRAG = !FIRST, YFRAG = FIRST, RELU = FIRST;
-    __shared__ __align__(16) float red[KSPLIT > 1 ? 3 * 16 * 64 : 1];
+    __shared__ __align__(16) float red[KSPLIT > 1 ? (KSPLIT - 1) * FBW * 16 * 64 : 1];
     const int nfb = N >> 5, nrb = R >> 4;
-    const int ftiles = KSPLIT == 1 ? (nfb + 3) / 4 : nfb;
-    int slot, ftile, m0, m_end, pm0;
-    if (!find_item(offsets, nslots, T, 32, ftiles, blockIdx.x, slot, ftile, m0, m_end, pm0)) return;
+    const int ftiles = (nfb + FBW - 1) / FBW;
+    const int slot = blockIdx.x / ftiles, ftile = blockIdx.x % ftiles;
     // the wave index as a scalar: the reduction range below must be wave-uniform in the
     // compiler's eyes too, because an MFMA under a lane mask still runs for every lane
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-    const int fb = KSPLIT == 1 ? ftile * 4 + wave : ftile;
+    const int fbi = wave / KSPLIT, part = wave % KSPLIT;   // feature block in the workgroup, share of the reduction
+    const int fb = ftile * FBW + fbi;
     const bool fb_ok = fb < nfb;
     const int per = (nrb + KSPLIT - 1) / KSPLIT;
-    const int kb_lo = KSPLIT == 1 ? 0 : min(wave * per, nrb), kb_hi = KSPLIT == 1 ? nrb : min(kb_lo + per, nrb);
-
+    const int kb_lo = min(part * per, nrb), kb_hi = min(kb_lo + per, nrb);
     const uint4* wp = Wp + ((size_t)slot * nfb + min(fb, nfb - 1)) * nrb * 64 + lane;
-    const uint4* xp;                                       // this lane's token operand at reduction step 0
-    size_t xstep;                                          // in uint4 units per reduction step
-    if (XFRAG) {
-        xp = (const uint4*)X + ((size_t)(pm0 >> 5) * (R >> 3) + (lane >> 5)) * 32 + (lane & 31);
-        xstep = 2 * 32;
-    } else {
-        int row = min(m0 + (lane & 31), m_end - 1);
-        if (fz.perm) row = fz.perm[row];
-        xp = (const uint4*)(X + (size_t)row * R + (lane >> 5) * 8);
-        xstep = 2;
-    }
-    f32x16 acc;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-    // two groups of G reduction steps are always in flight: while one group's
-    // MFMAs run, the next group's operands are already on their way
+
     uint4 wA[G], xA[G], wB[G], xB[G];
-    auto fetch = [&](uint4 (&w)[G], uint4 (&xv)[G], int g0) {
+    auto fetch_w = [&](uint4 (&w)[G], int g0) {
 #pragma unroll
-        for (int i = 0; i < G; ++i) {
-            const int kb = max(min(g0 + i, kb_hi - 1), 0);  // past the end: reloaded, not used
-            w[i] = wp[(size_t)kb * 64];
-            xv[i] = xp[(size_t)kb * xstep];
-        }
+        for (int i = 0; i < G; ++i) w[i] = wp[(size_t)max(min(g0 + i, kb_hi - 1), 0) * 64];   // past the end: reloaded, not used
     };
-    auto consume = [&](uint4 (&w)[G], uint4 (&xv)[G], int g0) {
-#pragma unroll
-        for (int i = 0; i < G; ++i) {
-            // steps past the end of the range multiply by a zero token operand
-            const uint4 xz = g0 + i < kb_hi ? xv[i] : make_uint4(0, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(w[i]), as_frag(xz), acc, 0, 0, 0);
+    fetch_w(wA, kb_lo);                                    // on its way before anything else is known
+
+    // this slot's rows and the padded rows before it (segments re-based to multiples of 32)
+    int seg_a = 0, seg_b = 0, pad_before = 0;
+    for (int base = 0; base < nslots; base += 64) {
+        const int k = base + lane;
+        int a = 0, b = 0;
+        if (k < nslots) {
+            a = min(max(offsets[k], 0), T);                 // clamps guard misuse
+            b = max(min(max(offsets[k + 1], 0), T), a);
         }
-    };
-    fetch(wA, xA, kb_lo);
-    for (int g0 = kb_lo; g0 < kb_hi; g0 += 2 * G) {
-        fetch(wB, xB, g0 + G);
-        __builtin_amdgcn_sched_barrier(0);
-        consume(wA, xA, g0);
-        __builtin_amdgcn_sched_barrier(0);
-        fetch(wA, xA, g0 + 2 * G);
-        __builtin_amdgcn_sched_barrier(0);
-        consume(wB, xB, g0 + G);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    if (KSPLIT > 1) {
-        if (wave > 0) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) red[((wave - 1) * 16 + i) * 64 + lane] = acc[i];
+        const int pad = (b - a + 31) & ~31;
+        const int pin = wave_incl_scan(pad, lane);
+        if (slot >= base && slot < base + 64) {
+            seg_a = __shfl(a, slot - base);
+            seg_b = __shfl(b, slot - base);
+            pad_before += __shfl(pin - pad, slot - base);
+            break;
         }
-        __syncthreads();
-        if (wave > 0) return;
-#pragma unroll
-        for (int w2 = 0; w2 < KSPLIT - 1; ++w2)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[i] += red[(w2 * 16 + i) * 64 + lane];
+        pad_before += __shfl(pin, 63);
     }
-    if (!fb_ok) return;
-    // accumulator register i of lane l: feature 8*(i/4) + 4*(l/32) + i%4, token l%32
-    uint16_t* ydst;
-    const uint16_t* rsrc = nullptr;
-    float gmul = 1.f;
-    if (YFRAG) {
-        ydst = Y + (((size_t)(pm0 >> 5) * (N >> 3) + fb * 4) * 32 + (lane & 31)) * 8 + (lane >> 5) * 4;
-    } else {
-        int row = m0 + (lane & 31);
-        if (row >= m_end) return;
-        if (fz.perm) {
-            row = fz.perm[row];
-            gmul = fz.gate[row];
-            if (fz.residual) rsrc = fz.residual + (size_t)row * N + fb * 32 + (lane >> 5) * 4;
+    seg_a = __builtin_amdgcn_readfirstlane(seg_a);
+    seg_b = __builtin_amdgcn_readfirstlane(seg_b);
+    pad_before = __builtin_amdgcn_readfirstlane(pad_before);
+    if (seg_b <= seg_a) return;                            // nothing routed to this slot
+
+    for (int m0 = seg_a; m0 < seg_b; m0 += 32) {
+        const int m_end = seg_b, pm0 = pad_before + (m0 - seg_a);
+        const uint4* xp;                                   // this lane's token operand at reduction step 0
+        size_t xstep;                                      // in uint4 units per reduction step
+        if (XFRAG) {
+            xp = (const uint4*)X + ((size_t)(pm0 >> 5) * (R >> 3) + (lane >> 5)) * 32 + (lane & 31);
+            xstep = 2 * 32;
+        } else {
+            int row = min(m0 + (lane & 31), m_end - 1);
+            if (fz.perm) row = fz.perm[row];
+            xp = (const uint4*)(X + (size_t)row * R + (lane >> 5) * 8);
+            xstep = 2;
         }
-        ydst = Y + (size_t)row * N + fb * 32 + (lane >> 5) * 4;
-    }
+        auto fetch_x = [&](uint4 (&xv)[G], int g0) {
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        float v0 = acc[4 * g], v1 = acc[4 * g + 1], v2 = acc[4 * g + 2], v3 = acc[4 * g + 3];
-        if (!YFRAG) apply_gate(v0, v1, v2, v3, gmul, rsrc ? rsrc + g * 8 : nullptr, fz.perm != nullptr);
-        if (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
-        uint2 o;
-        o.x = (uint32_t)smoe_f32_to_bf16(v0) | ((uint32_t)smoe_f32_to_bf16(v1) << 16);
-        o.y = (uint32_t)smoe_f32_to_bf16(v2) | ((uint32_t)smoe_f32_to_bf16(v3) << 16);
-        *(uint2*)(ydst + (YFRAG ? g * 32 * 8 : g * 8)) = o;
+            for (int i = 0; i < G; ++i) xv[i] = xp[(size_t)max(min(g0 + i, kb_hi - 1), 0) * xstep];
+        };
+        f32x16 acc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+        auto consume = [&](uint4 (&w)[G], uint4 (&xv)[G], int g0) {
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                // steps past the end of the range multiply by a zero token operand
+                const uint4 xz = g0 + i < kb_hi ? xv[i] : make_uint4(0, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(w[i]), as_frag(xz), acc, 0, 0, 0);
+            }
+        };
+        // two groups of G reduction steps are always in flight: while one group's
+        // MFMAs run, the next group's operands are already on their way
+        if (m0 != seg_a) fetch_w(wA, kb_lo);               // (the first row tile's were issued at the top)
+        fetch_x(xA, kb_lo);
+        for (int g0 = kb_lo; g0 < kb_hi; g0 += 2 * G) {
+            fetch_w(wB, g0 + G);
+            fetch_x(xB, g0 + G);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(wA, xA, g0);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch_w(wA, g0 + 2 * G);
+            fetch_x(xA, g0 + 2 * G);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(wB, xB, g0 + G);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (KSPLIT > 1) {
+            if (m0 != seg_a) __syncthreads();              // the previous row tile's sums have been read
+            if (part > 0) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) red[(((part - 1) * FBW + fbi) * 16 + i) * 64 + lane] = acc[i];
+            }
+            __syncthreads();
+            if (part == 0) {
+#pragma unroll
+                for (int w2 = 0; w2 < KSPLIT - 1; ++w2)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[i] += red[((w2 * FBW + fbi) * 16 + i) * 64 + lane];
+            }
+        }
+        if (part > 0 || !fb_ok) continue;
+        // accumulator register i of lane l: feature 8*(i/4) + 4*(l/32) + i%4, token l%32
+        uint16_t* ydst;
+        const uint16_t* rsrc = nullptr;
+        float gmul = 1.f;
+        if (YFRAG) {
+            ydst = Y + (((size_t)(pm0 >> 5) * (N >> 3) + fb * 4) * 32 + (lane & 31)) * 8 + (lane >> 5) * 4;
+        } else {
+            int row = m0 + (lane & 31);
+            if (row >= m_end) continue;
+            if (fz.perm) {
+                row = fz.perm[row];
+                gmul = fz.gate[row];
+                if (fz.residual) rsrc = fz.residual + (size_t)row * N + fb * 32 + (lane >> 5) * 4;
+            }
+            ydst = Y + (size_t)row * N + fb * 32 + (lane >> 5) * 4;
+        }
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            float v0 = acc[4 * g], v1 = acc[4 * g + 1], v2 = acc[4 * g + 2], v3 = acc[4 * g + 3];
+            if (!YFRAG) apply_gate(v0, v1, v2, v3, gmul, rsrc ? rsrc + g * 8 : nullptr, fz.perm != nullptr);
+            if (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
+            uint2 o;
+            o.x = (uint32_t)smoe_f32_to_bf16(v0) | ((uint32_t)smoe_f32_to_bf16(v1) << 16);
+            o.y = (uint32_t)smoe_f32_to_bf16(v2) | ((uint32_t)smoe_f32_to_bf16(v3) << 16);
+            *(uint2*)(ydst + (YFRAG ? g * 32 * 8 : g * 8)) = o;
+        }
     }
 }
 
-template <int KSPLIT, bool FIRST>
+template <int NWV, int KSPLIT, bool FIRST>
 void launch_small(const uint16_t* X, const void* Wp, const int32_t* offsets, int nslots, uint16_t* Y, int R,
                   int N, int T, const FuseArgs& fz, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
-    int mtiles = (T + 31) / 32 + nslots;
+    constexpr int FBW = NWV / KSPLIT;
+    (void)T;
     int nfb = N >> 5;
-    int ftiles = KSPLIT == 1 ? (nfb + 3) / 4 : nfb;
-    dim3 grid(XCDS * ((mtiles + XCDS - 1) / XCDS) * ftiles);
-    smoe_launch_timed(small_gemm_bf16<KSPLIT, FIRST>, grid, dim3(256), s, e0, e1, X, (const uint4*)Wp, offsets,
-                      nslots, T, Y, R, N, fz);
+    int ftiles = (nfb + FBW - 1) / FBW;
+    dim3 grid(nslots * ftiles);                            // one workgroup per (slot, feature tile)
+    smoe_launch_timed(small_gemm_bf16<NWV, KSPLIT, FIRST>, grid, dim3(NWV * 64), s, e0, e1, X, (const uint4*)Wp,
+                      offsets, nslots, T, Y, R, N, fz);
 }
 
 // Compute units per die, asked of the runtime once.
@@ -632,13 +674,13 @@ void launch_gemm(const uint16_t* X, const void* Wp, const int32_t* offsets, int 
                           (const uint4*)Wp, offsets, nslots, T, Y, R, N, fz);
 }
 
-constexpr int N_VARIANTS = 9;
+constexpr int N_VARIANTS = 10;
 
 template <bool FIRST>
 void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* offsets, int nslots,
                     uint16_t* Y, int R, int N, int T, const FuseArgs& fz, hipStream_t s, hipEvent_t e0,
                     hipEvent_t e1) {
-    if (R % 64 != 0 && v != 5 && v != 6) {   // d_model / d_ff are multiples of 32 by contract: 32-deep slices always fit
+    if (R % 64 != 0 && v != 5 && v != 6 && v < 9) {   // d_model / d_ff are multiples of 32 by contract: 32-deep slices always fit
         launch_gemm<1, 4, 4, 32, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1);
         return;
     }
@@ -650,8 +692,10 @@ void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* off
         case 4: launch_gemm<1, 1, 4, 64, 3, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  //  32 x 128
         case 7: launch_gemm<2, 4, 4, 64, 3, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  // 128 x 256, one wave per SIMD
         case 8: launch_gemm<1, 4, 8, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  // 128 x 256, 8 waves
-        case 5: launch_small<1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;   // 32 x 128, streaming
-        default: launch_small<4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  // 32 x 32, reduction split 4 ways
+        case 5: launch_small<4, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;   // 32 x 128, streaming
+        case 6: launch_small<4, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;   // 32 x 32, reduction split 4 ways
+        case 9: launch_small<4, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;   // 32 x 64, split 2
+        default: launch_small<4, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;
     }
 }
 

@@ -235,7 +235,7 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
     constexpr int THREADS = NWR * 64;
     // reduction steps whose operands are fetched together, so that one memory
     // round trip feeds several MFMAs: bounded by registers (1 + 3*NEB loads per step)
-    constexpr int G = NEB == 1 ? 8 : NEB == 2 ? 4 : NEB <= 5 ? 2 : 1;
+    constexpr int G = NEB == 1 ? 8 : NEB == 2 ? 6 : NEB <= 5 ? 2 : 1;
     float* part = smem;                           // [NWR waves][EP][RTP] partial logits
     float* sqp = smem + NWR * EP * RTP;           // [NWR waves][2 halves][RT] partial sums of squares
     __shared__ int32_t s_e2s[EP];
