@@ -15,16 +15,22 @@ between uses.  `value` = T * layers / step time: tokens through a MoE layer per
 second.
 
 Decode workload (c4): one step is one decode step (T=32 tokens, one token per
-stream) through `--decode-layers` layers; every `period` (16) steps the
-importance scores are read back, the update policy picks the new resident set
-and the changed slots are reloaded from the full expert bank -- all of that is
-inside the timed region.  `value` = T * layers * steps / time.
+stream) through `--decode-layers` layers; the resident set follows the
+importance scores inside the timed region.  `--updates sync` (default): every
+`period` (16) steps the scores are read back, the policy picks the new resident
+set and the changed slots are reloaded from the expert bank before the next
+step.  `--updates async`: the scores travel to the host behind the compute
+stream, smoe_update_begin plans the changes and smoe_update_tick, called
+between steps, loads one expert per spare slot on a second stream and switches
+the maps when a load has arrived (amortized, asynchronous loading).  `--bank
+pinned` keeps the bank in host memory, so loads cross PCIe.
+`value` = T * layers * steps / time.
 
 Prints ONE JSON line.  `roofline` is for the expert FFN's two grouped-GEMM
-launches: their duration is measured live with HIP events recorded on the
-launch stream around each product of every smoe_expert_ffn call of the timed
-region.  `cpu_baseline` times the CPU oracle on a bounded sample of the same
-workload on this machine's host cores.
+launches: their duration is measured live with HIP events attached to the two
+product dispatches of one layer call per sampled step of the timed region.
+`cpu_baseline` times the CPU oracle on a bounded sample of the same workload on
+this machine's host cores.
 """
 import argparse
 import json
@@ -50,14 +56,14 @@ def dev_t(a, dev):
     return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).to(dev)
 
 
-def make_layer(b, wl, cfg, l, experts, dev):
+def make_layer(b, wl, cfg, l, experts, dev, spare_slots=0, pinned_bank=False):
     """One bound layer with `experts` (bank order) uploaded; slots 0..K-1 hold the
     first K of them.  Returns (layer, device bank, host copies of layer data)."""
     import torch
     Wr = wl.router_weights(cfg, l)
     W1, W2 = wl.expert_bank(cfg, l, experts)
     lay = b.Layer(cfg.E, cfg.K, cfg.d_model, cfg.d_ff, cfg.T, cfg.dtype, router_w=torch.from_numpy(Wr),
-                  device=dev)
+                  device=dev, spare_slots=spare_slots)
     d1, d2 = dev_t(W1, dev), dev_t(W2, dev)
     en = lay.expert_norm_of(d1, d2)                  # |E_i| of the experts we hold; 1 elsewhere
     full = torch.ones(cfg.E, dtype=torch.float32, device=dev)
@@ -66,6 +72,10 @@ def make_layer(b, wl, cfg, l, experts, dev):
     for s in range(cfg.K):
         lay.set_resident(s, int(experts[s]), d1[s], d2[s])
     torch.cuda.synchronize()
+    if pinned_bank:                                  # the bank the updates read from lives in host memory
+        import numpy as np
+        d1 = torch.from_numpy(W1.view(np.int16)).pin_memory()
+        d2 = torch.from_numpy(W2.view(np.int16)).pin_memory()
     return lay, (d1, d2), (Wr, W1, W2)
 
 
@@ -77,6 +87,17 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--decode-layers", type=int, default=1,
                     help="c4 only: independent layers per decode step (6 exceeds the 256 MB Infinity Cache)")
+    ap.add_argument("--updates", default="sync", choices=["sync", "async", "none"],
+                    help="c4 only: how the resident set follows the scores. sync: all changes applied at the "
+                         "period boundary on the compute stream; async: smoe_update_begin/tick, loads on a second "
+                         "stream into a spare slot, spread over the following steps; none: never updated")
+    ap.add_argument("--bank", default="device", choices=["device", "pinned"],
+                    help="c4 only: where the full expert bank lives (pinned = host memory read over PCIe)")
+    ap.add_argument("--spare-slots", type=int, default=1, help="c4 --updates async: spare physical slots")
+    ap.add_argument("--max-ahead", type=int, default=2,
+                    help="c4 only: decode steps the host may enqueue ahead of the GPU (a serving loop reads each "
+                         "step's tokens before it can issue the next; unbounded run-ahead would also make "
+                         "'between two steps' meaningless for the asynchronous updates)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--separate-calls", action="store_true",
                     help="drive the layer through the five per-step calls instead of smoe_forward")
@@ -107,7 +128,9 @@ def main():
     experts = list(range(cfg.E)) if decode else list(s2e0)
     layers, banks, host0 = [], [], None
     for l in range(L):
-        lay, bank, host = make_layer(b, wl, cfg, l, experts, dev)
+        lay, bank, host = make_layer(b, wl, cfg, l, experts, dev,
+                                     spare_slots=args.spare_slots if (decode and args.updates == "async") else 0,
+                                     pinned_bank=decode and args.bank == "pinned")
         layers.append(lay)
         banks.append(bank if decode else None)       # prefill never reloads: free the bank copy
         if l == 0:
@@ -152,33 +175,48 @@ def main():
         xs_host = wl.decode_stream(cfg, warmup + steps)
         xs = dev_t(xs_host.reshape(-1, cfg.d_model), dev).view(warmup + steps, T, cfg.d_model)
 
-        def reset():
-            # back to the initial resident set, so the replay sees the same sequence of updates
-            for lay, (d1, d2) in zip(layers, banks):
-                lay.rebind()
-                for s in range(cfg.K):
-                    lay.set_resident(s, s, d1[s], d2[s])
-            torch.cuda.synchronize()
+        load_stream = torch.cuda.Stream()
+        n_samples = (steps + ev_stride - 1) // ev_stride
+        offs_log = torch.zeros(n_samples, cfg.K + 1, dtype=torch.int32, device=dev)   # offsets of the timed launches
+        score_host = [torch.zeros(cfg.E, dtype=torch.float32).pin_memory() for _ in layers]
+        score_ev = [torch.cuda.Event() for _ in layers]
+        score_due = [False] * L
+        ahead = max(1, args.max_ahead)
+        step_done = [torch.cuda.Event() for _ in range(ahead + 1)]
 
-        def run(first, n, timed, log_active=False):
+        def run(first, n, timed):
             swaps = 0
             for i in range(n):
                 sidx = first + i
+                if args.updates == "async":                  # between two steps; never waits for the GPU
+                    for l, (lay, (b1, b2)) in enumerate(zip(layers, banks)):
+                        swaps += lay.update_tick(b1, b2, load_stream)
+                        if score_due[l] and score_ev[l].query():
+                            lay.update_begin(score_host[l].numpy())
+                            score_due[l] = False
                 x = xs[sidx]
                 for l, lay in enumerate(layers):
-                    if timed and use_events and i % ev_stride == 0 and l == (i // ev_stride) % L:
+                    sampled = timed and i % ev_stride == 0 and l == (i // ev_stride) % L
+                    if sampled and use_events:
                         b.smoe_set_profile_events(lay.handle, *evs[i])
                         ev_used.append(i)
                     x = fwd(lay)(x, T, accumulate=0 if sidx % cfg.period == 0 else 1, residual=x)
-                    if log_active:
-                        off = lay.offsets.cpu().numpy()
-                        active_log.append(int((np.diff(off) > 0).sum()))
-                if (sidx + 1) % cfg.period == 0:
-                    for lay, (d1, d2) in zip(layers, banks):
-                        score = lay.score.cpu().numpy()              # the one host read-back per period
-                        for sl, ex in lay.select_resident(score):
-                            lay.set_resident(sl, ex, d1[ex], d2[ex])
-                            swaps += 1
+                    if sampled:
+                        offs_log[i // ev_stride].copy_(lay.offsets, non_blocking=True)
+                step_done[i % (ahead + 1)].record()
+                if i >= ahead:
+                    step_done[(i - ahead) % (ahead + 1)].synchronize()
+                if (sidx + 1) % cfg.period == 0 and args.updates != "none":
+                    for l, (lay, (d1, d2)) in enumerate(zip(layers, banks)):
+                        if args.updates == "async":          # scores travel to the host behind the compute stream
+                            score_host[l].copy_(lay.score, non_blocking=True)
+                            score_ev[l].record()
+                            score_due[l] = True
+                        else:
+                            score = lay.score.cpu().numpy()      # the one host read-back per period
+                            for sl, ex in lay.select_resident(score):
+                                lay.set_resident(sl, ex, d1[ex], d2[ex])
+                                swaps += 1
             torch.cuda.synchronize()
             return swaps
 
@@ -187,10 +225,7 @@ def main():
         t0 = time.perf_counter()
         swaps = run(warmup, steps, True)
         dt = time.perf_counter() - t0
-        # untimed replay of the same steps from the same state, to count active slots per FFN call
-        reset()
-        run(0, warmup, False)
-        run(warmup, steps, False, log_active=True)
+        active_log = (offs_log[:, 1:] > offs_log[:, :-1]).sum(dim=1).cpu().numpy().tolist()
 
     ms_per_step = dt / steps * 1e3
     value = T * L / (dt / steps)
@@ -251,7 +286,9 @@ def main():
               "entry": "five separate calls" if args.separate_calls else "smoe_forward (fused, 4 launches)",
               "step": "route+importance+permute+expert_ffn+combine over all layers"}
     if decode:
-        config.update(update_period=cfg.period, experts_swapped=swaps,
+        config.update(update_period=cfg.period, experts_swapped=swaps, updates=args.updates, bank=args.bank,
+                      host_steps_ahead=max(1, args.max_ahead),
+                      spare_slots=args.spare_slots if args.updates == "async" else 0,
                       step="one decode step: route+importance+permute+expert_ffn+combine, plus score "
                            "read-back, policy and slot reloads every update_period steps")
     out = {

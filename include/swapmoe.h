@@ -19,7 +19,8 @@
  *     Arguments are validated before anything is launched.
  *   - Unless marked "host", every pointer is a DEVICE pointer owned by the
  *     caller, who keeps it alive until the stream work that uses it is done.
- *     The library owns only the opaque handle (host memory).
+ *     The library owns only the opaque handle (host memory, plus one HIP
+ *     event per spare slot once smoe_update_tick has been used).
  *   - All matrices are row-major and dense.  Activations and expert weights
  *     have the dtype given in smoe_config (fp32, or bf16 stored as uint16 bit
  *     patterns); router weights, gates, norms and scores are fp32; indices and
@@ -59,12 +60,15 @@ typedef struct smoe_layer smoe_layer_t;
  * storage type of activations AND expert weights (SMOE_F32 or SMOE_BF16).
  * gate_mode: SMOE_GATE_FULL  gate = softmax over all E, read at the served expert;
  *            SMOE_GATE_RENORM the same divided by the resident experts' total.
+ * spare_slots: physical weight slots beyond K that smoe_update_tick loads into while the
+ *            K mapped ones keep serving (see the asynchronous update calls below).
  * Limits: E <= 256; K <= E; for SMOE_BF16, d_model and d_ff must be
  * multiples of 32 (the MFMA fragment width); max_tokens >= 1. */
 typedef struct {
     int32_t E, K, d_model, d_ff, max_tokens;
     int32_t dtype;
     int32_t gate_mode;
+    int32_t spare_slots;   /* extra physical slots for asynchronous loading, 0..8 (0: synchronous updates only) */
 } smoe_config;
 
 /* Creates a handle (host memory only; no HIP call is made).  *out is set to
@@ -187,6 +191,38 @@ int smoe_forward(smoe_layer_t* layer, const void* x, int T, const void* residual
                  int accumulate, int32_t* orig_expert, float* orig_gate, int32_t* slot, float* gate,
                  float* xnorm, int32_t* count, float* gsum, float* score, int32_t* perm,
                  int32_t* inv_perm, int32_t* offsets, void* stream);
+
+/* ---- Asynchronous, amortized resident-set update (Section 3.2 "Seamless ...
+ * Update"; Figure 5(ii)) ---------------------------------------------------
+ * Needs spare_slots >= 1.  The K virtual slots map onto K of the K+spare
+ * physical weight slots; a new expert is packed into a free physical slot on
+ * a separate stream while the forward pass keeps using the mapped ones, and
+ * the maps are switched between two hot calls once the load has finished.
+ * At most `spare_slots` loads are in flight, so an update of many experts is
+ * spread over as many steps as it needs instead of stalling one step.
+ *
+ * smoe_update_begin: host policy.  From the E importance scores (host array)
+ *   it plans the changes with the rule of smoe_select_resident, taking loads
+ *   already in flight as done, and replaces any earlier plan not yet started.
+ *   Returns the number of planned changes (>= 0) or a negative status.
+ * smoe_update_tick: call between two steps.  (1) Every in-flight load whose
+ *   copy has finished (event query; never waits) is committed: the slot and
+ *   expert maps and the slot's physical index change on compute_stream, so
+ *   the next hot call enqueued there serves the new expert, and the physical
+ *   slot it leaves becomes free once the work already enqueued has drained.
+ *   (2) While a physical slot is free and the plan is not empty, the next
+ *   expert's weights are packed from the bank on load_stream.  bank_w1 /
+ *   bank_w2 hold all E experts contiguously ([E][d_model][d_ff] and
+ *   [E][d_ff][d_model], the layer's dtype) in device memory or in pinned host
+ *   memory (then the copy engines bring the expert into a staging area of the
+ *   workspace first); they must stay valid until the load is done.
+ *   load_stream must differ from compute_stream for any overlap to happen.
+ *   Returns the number of commits made by this call (>= 0) or a negative status.
+ * smoe_update_pending: planned changes not yet committed (in flight included). */
+int smoe_update_begin(smoe_layer_t* layer, const float* score /*host, [E]*/);
+int smoe_update_tick(smoe_layer_t* layer, const void* bank_w1, const void* bank_w2, void* load_stream,
+                     void* compute_stream);
+int smoe_update_pending(const smoe_layer_t* layer);
 
 /* Measurement aid (not part of the paper's method): HIP events for the NEXT
  * smoe_expert_ffn (or smoe_forward) call on this handle.  The call attaches

@@ -32,7 +32,8 @@ _lib = C.CDLL(LIB_PATH)
 
 class smoe_config(C.Structure):
     _fields_ = [("E", C.c_int32), ("K", C.c_int32), ("d_model", C.c_int32), ("d_ff", C.c_int32),
-                ("max_tokens", C.c_int32), ("dtype", C.c_int32), ("gate_mode", C.c_int32)]
+                ("max_tokens", C.c_int32), ("dtype", C.c_int32), ("gate_mode", C.c_int32),
+                ("spare_slots", C.c_int32)]
 
 
 _vp, _i = C.c_void_p, C.c_int
@@ -47,6 +48,9 @@ _SIGS = {
     "smoe_set_resident": (C.c_int, [_vp, _i, _i, _vp, _vp, _vp]),
     "smoe_get_maps": (C.c_int, [_vp, _vp, _vp]),
     "smoe_select_resident": (C.c_int, [_vp, _vp, _vp, _vp]),
+    "smoe_update_begin": (C.c_int, [_vp, _vp]),
+    "smoe_update_tick": (C.c_int, [_vp, _vp, _vp, _vp, _vp]),
+    "smoe_update_pending": (C.c_int, [_vp]),
     "smoe_route": (C.c_int, [_vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp]),
     "smoe_importance": (C.c_int, [_vp, _vp, _vp, _vp, _i, _vp, _vp, _vp, _i, _vp]),
     "smoe_permute": (C.c_int, [_vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp]),
@@ -91,8 +95,8 @@ def _stream(stream=None):
     return s.cuda_stream
 
 
-def smoe_create(E, K, d_model, d_ff, max_tokens, dtype, gate_mode=SMOE_GATE_FULL):
-    cfg = smoe_config(E, K, d_model, d_ff, max_tokens, dtype, gate_mode)
+def smoe_create(E, K, d_model, d_ff, max_tokens, dtype, gate_mode=SMOE_GATE_FULL, spare_slots=0):
+    cfg = smoe_config(E, K, d_model, d_ff, max_tokens, dtype, gate_mode, spare_slots)
     h = _vp()
     _check(_lib.smoe_create(C.byref(cfg), C.byref(h)))
     return h
@@ -183,6 +187,19 @@ def _act_dtype(dtype):
     return torch.float32 if dtype == SMOE_F32 else torch.int16
 
 
+def smoe_update_begin(layer, score_host) -> int:
+    return _check(_lib.smoe_update_begin(layer, _ptr(score_host)))
+
+
+def smoe_update_tick(layer, bank_w1, bank_w2, load_stream, compute_stream=None) -> int:
+    return _check(_lib.smoe_update_tick(layer, _ptr(bank_w1), _ptr(bank_w2), _stream(load_stream),
+                                              _stream(compute_stream)))
+
+
+def smoe_update_pending(layer) -> int:
+    return _check(_lib.smoe_update_pending(layer))
+
+
 class Layer:
     """Handle + the device buffers it is bound to + reusable output buffers.
 
@@ -190,11 +207,12 @@ class Layer:
     """
 
     def __init__(self, E, K, d_model, d_ff, max_tokens, dtype, gate_mode=SMOE_GATE_FULL,
-                 router_w=None, expert_norm=None, device="cuda:0"):
+                 router_w=None, expert_norm=None, device="cuda:0", spare_slots=0):
         self.E, self.K, self.d_model, self.d_ff = E, K, d_model, d_ff
         self.max_tokens, self.dtype, self.gate_mode = max_tokens, dtype, gate_mode
         self.device = torch.device(device)
-        self.handle = smoe_create(E, K, d_model, d_ff, max_tokens, dtype, gate_mode)
+        self.spare_slots = spare_slots
+        self.handle = smoe_create(E, K, d_model, d_ff, max_tokens, dtype, gate_mode, spare_slots)
         dev = self.device
         nb = smoe_slot_weight_bytes(self.handle)
         self.slot_w1 = torch.empty(nb, dtype=torch.uint8, device=dev)
@@ -261,6 +279,16 @@ class Layer:
         ce = np.empty(self.K, np.int32)
         n = smoe_select_resident(self.handle, score_host, cs, ce)
         return [(int(cs[i]), int(ce[i])) for i in range(n)]
+
+    def update_begin(self, score_host):
+        import numpy as np
+        return smoe_update_begin(self.handle, np.ascontiguousarray(score_host, np.float32))
+
+    def update_tick(self, bank_w1, bank_w2, load_stream):
+        return smoe_update_tick(self.handle, bank_w1, bank_w2, load_stream)
+
+    def update_pending(self):
+        return smoe_update_pending(self.handle)
 
     def route(self, x, T):
         smoe_route(self.handle, x, T, self.orig_expert, self.orig_gate, self.slot, self.gate, self.xnorm)

@@ -39,6 +39,7 @@ smoe_ws_layout smoe_ws_plan(const smoe_config& c) {
     size_t off = 0;
     w.e2s = off;     off = align_up(off + (size_t)c.E * 4, 256);
     w.s2e = off;     off = align_up(off + (size_t)c.K * 4, 256);
+    w.phys = off;    off = align_up(off + (size_t)c.K * 4, 256);
     w.hist = off;    off = align_up(off + (size_t)smoe_sort_blocks(c.max_tokens) * c.K * 4, 256);
     w.hist32 = off;  off = align_up(off + (size_t)((c.max_tokens + 31) / 32) * c.K * 4, 256);
     // hidden activations: every segment is re-based to a multiple of 32 rows
@@ -48,6 +49,8 @@ smoe_ws_layout smoe_ws_plan(const smoe_config& c) {
     w.rsplit = off;
     if (c.dtype == SMOE_BF16) off = align_up(off + (size_t)((c.E + 31) / 32 * 32) * c.d_model * 2 * 3, 256);
     w.norm = off;    off = align_up(off + (size_t)c.E * 64 * 4, 256);      // smoe_expert_norm partial sums
+    // asynchronous loads from a host bank land here (copy engine) before they are packed into a slot
+    w.stage = off;   off = align_up(off + (size_t)c.spare_slots * 2 * c.d_model * c.d_ff * smoe_elem_size(c.dtype), 256);
     w.total = off;
     return w;
 }
@@ -71,6 +74,8 @@ int smoe_create(const smoe_config* cfg, smoe_layer_t** out) {
         return smoe_fail(SMOE_EINVAL, "smoe_create: unknown dtype %d", c.dtype);
     if (c.gate_mode != SMOE_GATE_FULL && c.gate_mode != SMOE_GATE_RENORM)
         return smoe_fail(SMOE_EINVAL, "smoe_create: unknown gate_mode %d", c.gate_mode);
+    if (c.spare_slots < 0 || c.spare_slots > 8)
+        return smoe_fail(SMOE_EINVAL, "smoe_create: spare_slots=%d outside [0,8]", c.spare_slots);
     if (c.dtype == SMOE_BF16 && (c.d_model % 32 || c.d_ff % 32))
         return smoe_fail(SMOE_EINVAL, "smoe_create: bf16 needs d_model and d_ff to be multiples of 32");
     if (c.dtype == SMOE_F32 && (c.d_model % 4 || c.d_ff % 4))
@@ -86,6 +91,9 @@ int smoe_create(const smoe_config* cfg, smoe_layer_t** out) {
 
 int smoe_destroy(smoe_layer_t* layer) {
     if (!layer) return smoe_fail(SMOE_EINVAL, "smoe_destroy: null handle");
+    for (auto& st : layer->staged) if (st.done) (void)hipEventDestroy(st.done);
+    for (hipEvent_t e : layer->event_pool) (void)hipEventDestroy(e);
+    for (hipEvent_t e : layer->released) if (e) (void)hipEventDestroy(e);
     delete layer;
     return SMOE_OK;
 }
@@ -97,7 +105,7 @@ size_t smoe_workspace_bytes(const smoe_layer_t* layer) {
 size_t smoe_slot_weight_bytes(const smoe_layer_t* layer) {
     if (!layer) return 0;
     const smoe_config& c = layer->cfg;
-    return (size_t)c.K * c.d_model * c.d_ff * smoe_elem_size(c.dtype);
+    return (size_t)(c.K + c.spare_slots) * c.d_model * c.d_ff * smoe_elem_size(c.dtype);
 }
 
 int smoe_bind(smoe_layer_t* L, const float* router_w, void* slot_w1, void* slot_w2,
@@ -117,6 +125,8 @@ int smoe_bind(smoe_layer_t* L, const float* router_w, void* slot_w1, void* slot_
     L->workspace = (char*)workspace;
     L->d_expert_to_slot = (int32_t*)(L->workspace + w.e2s);
     L->d_slot_to_expert = (int32_t*)(L->workspace + w.s2e);
+    L->d_phys = (int32_t*)(L->workspace + w.phys);
+    L->d_stage = L->workspace + w.stage;
     L->d_sort_hist = (int32_t*)(L->workspace + w.hist);
     L->d_hist32 = (int32_t*)(L->workspace + w.hist32);
     L->d_hidden = L->workspace + w.hidden;
@@ -127,6 +137,15 @@ int smoe_bind(smoe_layer_t* L, const float* router_w, void* slot_w1, void* slot_
     L->d_norm_partial = (float*)(L->workspace + w.norm);
     std::fill(L->slot_to_expert.begin(), L->slot_to_expert.end(), -1);
     std::fill(L->expert_to_slot.begin(), L->expert_to_slot.end(), -1);
+    L->phys.resize(L->cfg.K);
+    std::iota(L->phys.begin(), L->phys.end(), 0);
+    L->free_phys.clear();
+    for (int p = L->cfg.K + L->cfg.spare_slots - 1; p >= L->cfg.K; --p) L->free_phys.push_back(p);
+    L->free_stage.clear();
+    for (int i = L->cfg.spare_slots - 1; i >= 0; --i) L->free_stage.push_back(i);
+    L->plan.clear();
+    for (auto& st : L->staged) L->event_pool.push_back(st.done);   // loads of the old binding are forgotten
+    L->staged.clear();
     L->slots_set = 0;
     L->bound = true;
     return SMOE_OK;
@@ -176,8 +195,14 @@ int smoe_set_resident(smoe_layer_t* L, int slot, int expert, const void* w1_src,
     hipStream_t s = as_stream(stream);
     int rc0 = ensure_workspace(L, s);
     if (rc0) return rc0;
+    for (const auto& st : L->staged)
+        if (st.slot == slot || st.expert == expert)
+            return smoe_fail(SMOE_ESTATE, "smoe_set_resident: slot %d / expert %d has an asynchronous load in flight",
+                             st.slot, st.expert);
     int old = L->slot_to_expert[slot];
-    int rc = smoe_launch_load_slot(L, slot, expert, old, w1_src, w2_src, s);
+    int rc = smoe_launch_pack_slot(L, L->phys[slot], w1_src, w2_src, s);
+    if (rc) return rc;
+    rc = smoe_launch_set_map(L, slot, expert, old, L->phys[slot], s);
     if (rc) return rc;
     if (old >= 0) L->expert_to_slot[old] = -1; else L->slots_set += 1;
     L->slot_to_expert[slot] = expert;
@@ -185,13 +210,14 @@ int smoe_set_resident(smoe_layer_t* L, int slot, int expert, const void* w1_src,
     return SMOE_OK;
 }
 
-int smoe_select_resident(const smoe_layer_t* L, const float* score, int32_t* changed_slots,
-                         int32_t* changed_experts) {
-    if (!L) return smoe_fail(SMOE_EINVAL, "smoe_select_resident: null handle");
-    if (!score || !changed_slots || !changed_experts)
-        return smoe_fail(SMOE_EINVAL, "smoe_select_resident: null argument");
-    const int E = L->cfg.E, K = L->cfg.K;
-    // rank experts: higher score first, lower id first among equals
+// The update rule: the new resident set is the K best-scored experts (higher
+// score first, lower id first among equals); experts that stay keep their slot;
+// the freed slots, in ascending order, receive the newcomers in descending score.
+// s2e / e2s are the maps the plan starts from.  Returns the number of changes, -1
+// if the maps are inconsistent.
+static int plan_changes(const smoe_config& c, const float* score, const std::vector<int32_t>& s2e,
+                        const std::vector<int32_t>& e2s, int32_t* changed_slots, int32_t* changed_experts) {
+    const int E = c.E, K = c.K;
     std::vector<int> rank(E);
     std::iota(rank.begin(), rank.end(), 0);
     std::sort(rank.begin(), rank.end(), [&](int a, int b) {
@@ -202,15 +228,151 @@ int smoe_select_resident(const smoe_layer_t* L, const float* score, int32_t* cha
     // walk the free slots upwards and the newcomers downwards in score
     int n = 0, ri = 0;
     for (int s = 0; s < K; ++s) {
-        int cur = L->slot_to_expert[s];
+        int cur = s2e[s];
         if (cur >= 0 && wanted[cur]) continue;
-        while (ri < K && L->expert_to_slot[rank[ri]] >= 0) ++ri;
-        if (ri >= K) return smoe_fail(SMOE_ESTATE, "smoe_select_resident: inconsistent maps");
+        while (ri < K && e2s[rank[ri]] >= 0) ++ri;
+        if (ri >= K) return -1;
         changed_slots[n] = s;
         changed_experts[n] = rank[ri++];
         ++n;
     }
     return n;
+}
+
+int smoe_select_resident(const smoe_layer_t* L, const float* score, int32_t* changed_slots,
+                         int32_t* changed_experts) {
+    if (!L) return smoe_fail(SMOE_EINVAL, "smoe_select_resident: null handle");
+    if (!score || !changed_slots || !changed_experts)
+        return smoe_fail(SMOE_EINVAL, "smoe_select_resident: null argument");
+    int n = plan_changes(L->cfg, score, L->slot_to_expert, L->expert_to_slot, changed_slots, changed_experts);
+    if (n < 0) return smoe_fail(SMOE_ESTATE, "smoe_select_resident: inconsistent maps");
+    return n;
+}
+
+// ---- asynchronous, amortized update ----------------------------------------
+
+int smoe_update_begin(smoe_layer_t* L, const float* score) {
+    if (!L) return smoe_fail(SMOE_EINVAL, "smoe_update_begin: null handle");
+    if (!L->bound) return smoe_fail(SMOE_ESTATE, "smoe_update_begin: call smoe_bind first");
+    if (L->cfg.spare_slots < 1) return smoe_fail(SMOE_ESTATE, "smoe_update_begin: the layer has no spare slot");
+    if (!score) return smoe_fail(SMOE_EINVAL, "smoe_update_begin: null score");
+    if (L->slots_set != L->cfg.K) return smoe_fail(SMOE_ESTATE, "smoe_update_begin: not every slot holds an expert");
+    // loads in flight count as done
+    std::vector<int32_t> s2e = L->slot_to_expert, e2s = L->expert_to_slot;
+    for (const auto& st : L->staged) {
+        e2s[s2e[st.slot]] = -1;
+        s2e[st.slot] = st.expert;
+        e2s[st.expert] = st.slot;
+    }
+    std::vector<int32_t> cs(L->cfg.K), ce(L->cfg.K);
+    int n = plan_changes(L->cfg, score, s2e, e2s, cs.data(), ce.data());
+    if (n < 0) return smoe_fail(SMOE_ESTATE, "smoe_update_begin: inconsistent maps");
+    L->plan.clear();
+    for (int i = 0; i < n; ++i) {
+        bool busy = false;                       // a slot with a load in flight keeps what is coming
+        for (const auto& st : L->staged) busy |= st.slot == cs[i];
+        if (!busy) L->plan.emplace_back(cs[i], ce[i]);
+    }
+    return (int)L->plan.size();
+}
+
+int smoe_update_pending(const smoe_layer_t* L) {
+    if (!L) return smoe_fail(SMOE_EINVAL, "smoe_update_pending: null handle");
+    return (int)(L->plan.size() + L->staged.size());
+}
+
+int smoe_update_tick(smoe_layer_t* L, const void* bank_w1, const void* bank_w2, void* load_stream,
+                     void* compute_stream) {
+    if (!L) return smoe_fail(SMOE_EINVAL, "smoe_update_tick: null handle");
+    if (!L->bound) return smoe_fail(SMOE_ESTATE, "smoe_update_tick: call smoe_bind first");
+    if (L->cfg.spare_slots < 1) return smoe_fail(SMOE_ESTATE, "smoe_update_tick: the layer has no spare slot");
+    if (!bank_w1 || !bank_w2) return smoe_fail(SMOE_EINVAL, "smoe_update_tick: null bank");
+    if (misaligned(bank_w1, 16) || misaligned(bank_w2, 16))
+        return smoe_fail(SMOE_EINVAL, "smoe_update_tick: banks must be 16-byte aligned");
+    hipStream_t ls = as_stream(load_stream), cs = as_stream(compute_stream);
+    const smoe_config& c = L->cfg;
+    if (L->released.empty()) L->released.assign(c.K + c.spare_slots, nullptr);
+    int commits = 0;
+    // (1) commit what has arrived
+    for (size_t i = 0; i < L->staged.size();) {
+        smoe_layer::Staged st = L->staged[i];
+        hipError_t q = hipEventQuery(st.done);
+        if (q == hipErrorNotReady) { ++i; continue; }
+        if (q != hipSuccess) return smoe_check_hip(q, "smoe_update_tick: load event");
+        // the load has completed, so work submitted from now on sees its writes: no stream wait needed
+        int rc = SMOE_OK;
+        const int old_expert = L->slot_to_expert[st.slot], old_phys = L->phys[st.slot];
+        rc = smoe_launch_set_map(L, st.slot, st.expert, old_expert, st.phys, cs);
+        if (rc) return rc;
+        // work enqueued before this point may still read the physical slot that was just unmapped
+        if (!L->released[old_phys]) {
+            rc = smoe_check_hip(hipEventCreateWithFlags(&L->released[old_phys], hipEventDisableTiming),
+                                "smoe_update_tick: event");
+            if (rc) return rc;
+        }
+        rc = smoe_check_hip(hipEventRecord(L->released[old_phys], cs), "smoe_update_tick: release event");
+        if (rc) return rc;
+        L->expert_to_slot[old_expert] = -1;
+        L->slot_to_expert[st.slot] = st.expert;
+        L->expert_to_slot[st.expert] = st.slot;
+        L->phys[st.slot] = st.phys;
+        L->free_phys.push_back(old_phys);
+        L->free_stage.push_back(st.stage);
+        L->event_pool.push_back(st.done);
+        L->staged.erase(L->staged.begin() + i);
+        ++commits;
+    }
+    // (2) start the next loads
+    const size_t per = (size_t)c.d_model * c.d_ff * smoe_elem_size(c.dtype);   // bytes per matrix
+    // A bank in host memory is brought over by the copy engines into the staging area and packed from
+    // there: a kernel that reads host memory directly fills every CU's memory pipeline with slow PCIe
+    // reads and slows the forward pass it is meant to overlap with.
+    int host_bank = -1;                                        // asked of the runtime only when a load starts
+    while (!L->plan.empty() && !L->free_phys.empty() && !L->free_stage.empty()) {
+        const int slot = L->plan.front().first, expert = L->plan.front().second;
+        L->plan.erase(L->plan.begin());
+        if (L->expert_to_slot[expert] >= 0) continue;          // became resident by another route
+        smoe_layer::Staged st;
+        st.slot = slot;
+        st.expert = expert;
+        st.phys = L->free_phys.back();
+        st.stage = L->free_stage.back();
+        if (!L->event_pool.empty()) {
+            st.done = L->event_pool.back();
+            L->event_pool.pop_back();
+        } else {
+            int rc = smoe_check_hip(hipEventCreateWithFlags(&st.done, hipEventDisableTiming), "smoe_update_tick: event");
+            if (rc) return rc;
+        }
+        int rc = SMOE_OK;
+        if (L->released[st.phys])
+            rc = smoe_check_hip(hipStreamWaitEvent(ls, L->released[st.phys], 0), "smoe_update_tick: stream order");
+        const char* src1 = (const char*)bank_w1 + (size_t)expert * per;
+        const char* src2 = (const char*)bank_w2 + (size_t)expert * per;
+        if (host_bank < 0) {
+            hipPointerAttribute_t at;
+            if (hipPointerGetAttributes(&at, bank_w1) == hipSuccess) host_bank = at.type == hipMemoryTypeHost;
+            else { (void)hipGetLastError(); host_bank = 0; }   // unregistered memory: treated as device-readable
+        }
+        if (!rc && host_bank == 1) {
+            char* s1 = L->d_stage + (size_t)st.stage * 2 * per;
+            rc = smoe_check_hip(hipMemcpyAsync(s1, src1, per, hipMemcpyHostToDevice, ls), "smoe_update_tick: copy");
+            if (!rc) rc = smoe_check_hip(hipMemcpyAsync(s1 + per, src2, per, hipMemcpyHostToDevice, ls),
+                                         "smoe_update_tick: copy");
+            src1 = s1;
+            src2 = s1 + per;
+        }
+        if (!rc) rc = smoe_launch_pack_slot(L, st.phys, src1, src2, ls);
+        if (!rc) rc = smoe_check_hip(hipEventRecord(st.done, ls), "smoe_update_tick: load event");
+        if (rc) {
+            L->event_pool.push_back(st.done);
+            return rc;
+        }
+        L->free_phys.pop_back();
+        L->free_stage.pop_back();
+        L->staged.push_back(st);
+    }
+    return commits;
 }
 
 // ---- the hot calls: validate, then hand over to the launchers -------------

@@ -198,6 +198,7 @@ __device__ __forceinline__ bf16x8 as_frag(uint4 v) {
 //   second product: row r is written to out[perm[r]] = gate[perm[r]] * y (+ residual[perm[r]]),
 //                   i.e. y = G(x)_i E_i(x) lands in token order (no y_perm).
 struct FuseArgs {
+    const int32_t* phys;      // virtual slot -> physical weight slot, [nslots] (always set)
     const int32_t* perm;
     const float* gate;
     const uint16_t* residual;
@@ -466,6 +467,7 @@ __global__ __launch_bounds__(NW * 64, OCC) void grouped_gemm_bf16(
         const int mt = (int)(g / ftiles), ftile = (int)(g % ftiles);
         int slot, m0, m_end, pm0;
         row_tile_at(map, nslots, BT, mt, slot, m0, m_end, pm0);
+        slot = __builtin_amdgcn_readfirstlane(fz.phys[slot]);   // from here on: where the weights live
         const int nbf = min(MAXB, (m_end - m0 + 31) >> 5);    // token blocks that hold real rows
         TileSwitch<AF, MAXB, MAXB, NW, BKT, PD, !FIRST, FIRST, FIRST>::go(nbf, X, Wp, Y, R, N, slot, m0, m_end,
                                                                          pm0, ftile, xs, fz);
@@ -509,7 +511,7 @@ __global__ __launch_bounds__(NWV * 64) void small_gemm_bf16(
     const bool fb_ok = fb < nfb;
     const int per = (nrb + KSPLIT - 1) / KSPLIT;
     const int kb_lo = min(part * per, nrb), kb_hi = min(kb_lo + per, nrb);
-    const uint4* wp = Wp + ((size_t)slot * nfb + min(fb, nfb - 1)) * nrb * 64 + lane;
+    const uint4* wp = Wp + ((size_t)fz.phys[slot] * nfb + min(fb, nfb - 1)) * nrb * 64 + lane;
 
     uint4 wA[G], xA[G], wB[G], xB[G];
     auto fetch_w = [&](uint4 (&w)[G], int g0) {
@@ -725,7 +727,7 @@ int smoe_launch_ffn_bf16(const smoe_layer* L, const uint16_t* x_perm, const int3
     int v1, v2;
     pick_variants(c, T, v1, v2);
     uint16_t* h = (uint16_t*)L->d_hidden;
-    const FuseArgs none{nullptr, nullptr, nullptr};
+    const FuseArgs none{L->d_phys, nullptr, nullptr, nullptr};
     launch_variant<true>(v1, x_perm, L->slot_w1, offsets, c.K, h, c.d_model, c.d_ff, T, none, s, L->prof_ev[0], L->prof_ev[1]);
     launch_variant<false>(v2, h, L->slot_w2, offsets, c.K, y_perm, c.d_ff, c.d_model, T, none, s, L->prof_ev[2], L->prof_ev[3]);
     return smoe_check_hip(hipGetLastError(), "smoe_expert_ffn launch");
@@ -740,7 +742,7 @@ int smoe_launch_ffn_bf16_fused(const smoe_layer* L, const uint16_t* x, const int
     int v1, v2;
     pick_variants(c, T, v1, v2);
     uint16_t* h = (uint16_t*)L->d_hidden;
-    const FuseArgs gather{perm, nullptr, nullptr}, scatter{perm, gate, residual};
+    const FuseArgs gather{L->d_phys, perm, nullptr, nullptr}, scatter{L->d_phys, perm, gate, residual};
     launch_variant<true>(v1, x, L->slot_w1, offsets, c.K, h, c.d_model, c.d_ff, T, gather, s, L->prof_ev[0], L->prof_ev[1]);
     launch_variant<false>(v2, h, L->slot_w2, offsets, c.K, out, c.d_ff, c.d_model, T, scatter, s, L->prof_ev[2], L->prof_ev[3]);
     return smoe_check_hip(hipGetLastError(), "smoe_forward: FFN launch");

@@ -30,7 +30,8 @@ __device__ __forceinline__ bool find_tile(const int32_t* __restrict__ offsets, i
 template <bool RELU>
 __global__ __launch_bounds__(256) void grouped_gemm_f32(const float* __restrict__ X,
                                                         const float* __restrict__ W,
-                                                        const int32_t* __restrict__ offsets, int nslots, int T,
+                                                        const int32_t* __restrict__ offsets,
+                                                        const int32_t* __restrict__ phys, int nslots, int T,
                                                         float* __restrict__ Y, int R, int N) {
     __shared__ float xs[BM][BK + 1];
     __shared__ __align__(16) float ws[BK][BN];
@@ -38,7 +39,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32(const float* __restrict_
     if (!find_tile(offsets, nslots, T, blockIdx.x, BM, slot, m0, m_end)) return;
     const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
     const int n0 = blockIdx.y * BN;
-    const float* Wk = W + (size_t)slot * R * N;
+    const float* Wk = W + (size_t)phys[slot] * R * N;
     float acc[2][4] = {};
     for (int k0 = 0; k0 < R; k0 += BK) {
         __syncthreads();
@@ -86,9 +87,10 @@ int smoe_launch_ffn_f32(const smoe_layer* L, const float* x_perm, const int32_t*
     const int mtiles = (T + BM - 1) / BM + c.K;            // upper bound; surplus workgroups exit
     float* h = (float*)L->d_hidden;
     smoe_launch_timed(grouped_gemm_f32<true>, dim3(mtiles, (c.d_ff + BN - 1) / BN), dim3(256), s, L->prof_ev[0],
-                      L->prof_ev[1], x_perm, (const float*)L->slot_w1, offsets, c.K, T, h, c.d_model, c.d_ff);
+                      L->prof_ev[1], x_perm, (const float*)L->slot_w1, offsets, L->d_phys, c.K, T, h, c.d_model,
+                      c.d_ff);
     smoe_launch_timed(grouped_gemm_f32<false>, dim3(mtiles, (c.d_model + BN - 1) / BN), dim3(256), s,
-                      L->prof_ev[2], L->prof_ev[3], (const float*)h, (const float*)L->slot_w2, offsets, c.K, T,
+                      L->prof_ev[2], L->prof_ev[3], (const float*)h, (const float*)L->slot_w2, offsets, L->d_phys, c.K, T,
                       y_perm, c.d_ff, c.d_model);
     return smoe_check_hip(hipGetLastError(), "smoe_expert_ffn launch");
 }

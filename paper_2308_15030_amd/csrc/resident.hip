@@ -15,17 +15,19 @@
 
 namespace {
 
-__global__ void clear_maps_kernel(int32_t* e2s, int E, int32_t* s2e, int K) {
+__global__ void clear_maps_kernel(int32_t* e2s, int E, int32_t* s2e, int32_t* phys, int K) {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < E) e2s[i] = -1;
-    if (i < K) s2e[i] = -1;
+    if (i < K) { s2e[i] = -1; phys[i] = i; }
 }
 
-__global__ void set_map_kernel(int32_t* e2s, int32_t* s2e, int slot, int expert, int old_expert) {
+__global__ void set_map_kernel(int32_t* e2s, int32_t* s2e, int32_t* phys, int slot, int expert, int old_expert,
+                               int p) {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
         if (old_expert >= 0) e2s[old_expert] = -1;
         e2s[expert] = slot;
         s2e[slot] = expert;
+        phys[slot] = p;
     }
 }
 
@@ -108,12 +110,11 @@ __global__ void norm_finish_kernel(const float* __restrict__ partial, int n, flo
 int smoe_launch_clear_maps(const smoe_layer* L, hipStream_t s) {
     int n = L->cfg.E > L->cfg.K ? L->cfg.E : L->cfg.K;
     hipLaunchKernelGGL(clear_maps_kernel, dim3((n + 255) / 256), dim3(256), 0, s, L->d_expert_to_slot,
-                       L->cfg.E, L->d_slot_to_expert, L->cfg.K);
+                       L->cfg.E, L->d_slot_to_expert, L->d_phys, L->cfg.K);
     return smoe_check_hip(hipGetLastError(), "smoe_set_resident: map reset");
 }
 
-int smoe_launch_load_slot(const smoe_layer* L, int slot, int expert, int old_expert,
-                          const void* w1_src, const void* w2_src, hipStream_t s) {
+int smoe_launch_pack_slot(const smoe_layer* L, int slot, const void* w1_src, const void* w2_src, hipStream_t s) {
     const smoe_config& c = L->cfg;
     const size_t per = (size_t)c.d_model * c.d_ff;               // elements per matrix
     if (c.dtype == SMOE_BF16) {
@@ -133,9 +134,13 @@ int smoe_launch_load_slot(const smoe_layer* L, int slot, int expert, int old_exp
         hipLaunchKernelGGL(copy16_kernel, grid, dim3(256), 0, s, (const uint4*)w2_src, n16,
                            (uint4*)((float*)L->slot_w2 + (size_t)slot * per));
     }
+    return smoe_check_hip(hipGetLastError(), "expert load launch");
+}
+
+int smoe_launch_set_map(const smoe_layer* L, int slot, int expert, int old_expert, int phys, hipStream_t s) {
     hipLaunchKernelGGL(set_map_kernel, dim3(1), dim3(64), 0, s, L->d_expert_to_slot, L->d_slot_to_expert,
-                       slot, expert, old_expert);
-    return smoe_check_hip(hipGetLastError(), "smoe_set_resident launch");
+                       L->d_phys, slot, expert, old_expert, phys);
+    return smoe_check_hip(hipGetLastError(), "map update launch");
 }
 
 int smoe_launch_expert_norm(const smoe_layer* L, const void* w1, const void* w2, int n, float* out,

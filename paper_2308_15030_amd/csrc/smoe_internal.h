@@ -20,6 +20,20 @@ struct smoe_layer {
     int slots_set = 0;                       // number of slots that hold an expert
     std::vector<int32_t> slot_to_expert;     // host copies of the maps
     std::vector<int32_t> expert_to_slot;
+    std::vector<int32_t> phys;               // virtual slot -> physical weight slot (host copy)
+    std::vector<int32_t> free_phys;          // physical slots no virtual slot maps to
+
+    // asynchronous update: the plan, and one record per load in flight
+    struct Staged {
+        int slot = -1, expert = -1, phys = -1, stage = -1;
+        hipEvent_t done = nullptr;           // recorded on the load stream after the pack
+    };
+    std::vector<std::pair<int, int>> plan;   // (slot, expert) changes not started yet, in order
+    std::vector<Staged> staged;              // loads in flight
+    std::vector<hipEvent_t> event_pool;      // spare events, owned by the handle
+    std::vector<int> free_stage;             // staging areas (one per spare slot) not in use
+    char* d_stage = nullptr;                 // [spare_slots][2 matrices], bank layout: landing area of host-bank copies
+    std::vector<hipEvent_t> released;        // per physical slot: compute-stream event after which it may be overwritten
 
     // caller-owned device buffers
     const float* router_w = nullptr;
@@ -31,6 +45,7 @@ struct smoe_layer {
     // carved out of the workspace (device)
     int32_t* d_expert_to_slot = nullptr;     // [E]
     int32_t* d_slot_to_expert = nullptr;     // [K]
+    int32_t* d_phys = nullptr;               // [K] physical weight slot of each virtual slot
     int32_t* d_sort_hist = nullptr;          // [sort blocks, K]
     int32_t* d_hist32 = nullptr;             // fused path: [ceil(max_tokens/32), K] from the router
     void* d_hidden = nullptr;                // [max_tokens, d_ff] activations of the FFN
@@ -44,7 +59,7 @@ struct smoe_layer {
 };
 
 struct smoe_ws_layout {
-    size_t e2s, s2e, hist, hist32, hidden, partial, rsplit, norm, total;
+    size_t e2s, s2e, phys, hist, hist32, hidden, partial, rsplit, norm, stage, total;
 };
 smoe_ws_layout smoe_ws_plan(const smoe_config& c);
 
@@ -78,8 +93,10 @@ int smoe_launch_ffn_bf16(const smoe_layer* L, const uint16_t* x_perm, const int3
                          uint16_t* y_perm, hipStream_t s);
 int smoe_launch_combine(const smoe_layer* L, const void* y_perm, const int32_t* inv_perm,
                         const float* gate, const void* residual, int T, void* out, hipStream_t s);
-int smoe_launch_load_slot(const smoe_layer* L, int slot, int expert, int old_expert,
-                          const void* w1_src, const void* w2_src, hipStream_t s);
+// packs / copies one expert's two matrices into physical slot `phys`
+int smoe_launch_pack_slot(const smoe_layer* L, int phys, const void* w1_src, const void* w2_src, hipStream_t s);
+// slot now serves `expert` from physical slot `phys` (old_expert, if any, leaves the maps)
+int smoe_launch_set_map(const smoe_layer* L, int slot, int expert, int old_expert, int phys, hipStream_t s);
 int smoe_launch_expert_norm(const smoe_layer* L, const void* w1, const void* w2, int n, float* out,
                             hipStream_t s);
 int smoe_launch_clear_maps(const smoe_layer* L, hipStream_t s);

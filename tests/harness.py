@@ -42,7 +42,7 @@ class Case:
     """
 
     def __init__(self, cfg: wl.MoEConfig, layer: int = 0, resident=None, bank_experts=None,
-                 gate_mode=0, x=None, router_scale=1.0, device="cuda:0"):
+                 gate_mode=0, x=None, router_scale=1.0, device="cuda:0", spare_slots=0):
         from paper_2308_15030_amd import binding as b
         self.b = b
         self.cfg, self.layer_idx = cfg, layer
@@ -66,7 +66,7 @@ class Case:
         self.en_oracle = np.ones(cfg.E, np.float64)
         self.en_oracle[self.bank_ids] = oracle.expert_norm(W1, W2)
         self.L = b.Layer(cfg.E, cfg.K, cfg.d_model, cfg.d_ff, max(self.T, 1), cfg.dtype, gate_mode,
-                         router_w=torch.from_numpy(self.Wr), device=device)
+                         router_w=torch.from_numpy(self.Wr), device=device, spare_slots=spare_slots)
         en_dev = self.L.expert_norm_of(self.d_W1, self.d_W2)
         full = torch.ones(cfg.E, dtype=torch.float32, device=device)
         full[torch.tensor(self.bank_ids, device=device)] = en_dev
