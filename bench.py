@@ -91,6 +91,14 @@ def main():
                     help="c4 only: how the resident set follows the scores. sync: all changes applied at the "
                          "period boundary on the compute stream; async: smoe_update_begin/tick, loads on a second "
                          "stream into a spare slot, spread over the following steps; none: never updated")
+    ap.add_argument("--policy", default="importance", choices=["importance", "count", "static", "lru"],
+                    help="c4 only: what ranks the experts at an update. importance: the Eq. 1 score; count: tokens "
+                         "per expert (the 'simple scheduling' ablation); static: the K experts of largest |E_i|, "
+                         "never updated (magnitude pruning); lru: load-on-miss after every step, least recently "
+                         "used slot evicted ('on demand' caching; --updates sync only)")
+    ap.add_argument("--hit-rate", action="store_true",
+                    help="c4 only: also log, per step, how many tokens found their own top-1 expert resident "
+                         "(two small device copies per step inside the timed region)")
     ap.add_argument("--bank", default="device", choices=["device", "pinned"],
                     help="c4 only: where the full expert bank lives (pinned = host memory read over PCIe)")
     ap.add_argument("--spare-slots", type=int, default=1, help="c4 --updates async: spare physical slots")
@@ -175,7 +183,23 @@ def main():
         xs_host = wl.decode_stream(cfg, warmup + steps)
         xs = dev_t(xs_host.reshape(-1, cfg.d_model), dev).view(warmup + steps, T, cfg.d_model)
 
+        if args.policy == "lru" and args.updates != "sync":
+            sys.exit("bench.py: --policy lru needs --updates sync")
+        if args.policy == "static":
+            args.updates = "none"
+            for lay, (d1, d2) in zip(layers, banks):           # resident set = the K largest experts by |E_i|
+                top = torch.argsort(lay.expert_norm, descending=True)[:cfg.K].cpu().tolist()
+                lay.rebind()
+                for sl, ex in enumerate(top):
+                    lay.set_resident(sl, ex, d1[ex], d2[ex])
+            torch.cuda.synchronize()
         load_stream = torch.cuda.Stream()
+        oe_log = torch.zeros(steps, T, dtype=torch.int32, device=dev) if args.hit_rate else None
+        e2s_log = np.zeros((steps, cfg.E), np.int32)
+        last_use = [np.zeros(cfg.K, np.int64) for _ in layers]    # lru: step of each slot's last use
+
+        def rank_tensor(lay):
+            return lay.count.to(torch.float32) if args.policy == "count" else lay.score
         n_samples = (steps + ev_stride - 1) // ev_stride
         offs_log = torch.zeros(n_samples, cfg.K + 1, dtype=torch.int32, device=dev)   # offsets of the timed launches
         score_host = [torch.zeros(cfg.E, dtype=torch.float32).pin_memory() for _ in layers]
@@ -203,17 +227,32 @@ def main():
                     x = fwd(lay)(x, T, accumulate=0 if sidx % cfg.period == 0 else 1, residual=x)
                     if sampled:
                         offs_log[i // ev_stride].copy_(lay.offsets, non_blocking=True)
+                    if timed and args.hit_rate and l == 0:
+                        oe_log[i].copy_(lay.orig_expert, non_blocking=True)
+                        e2s_log[i] = lay.maps()[1]
+                    if args.policy == "lru":                       # load what was missed, evict the stalest slots
+                        oe = lay.orig_expert.cpu().numpy()
+                        s2e, e2s = lay.maps()
+                        used = e2s[oe]
+                        last_use[l][used[used >= 0]] = sidx + 1
+                        missed, cnt = np.unique(oe[used < 0], return_counts=True)
+                        d1, d2 = banks[l]
+                        victims = [int(v) for v in np.argsort(last_use[l], kind="stable") if last_use[l][v] <= sidx]
+                        for ex, sl in zip(missed[np.argsort(-cnt, kind="stable")], victims):
+                            lay.set_resident(sl, int(ex), d1[int(ex)], d2[int(ex)])
+                            last_use[l][sl] = sidx + 1
+                            swaps += 1
                 step_done[i % (ahead + 1)].record()
                 if i >= ahead:
                     step_done[(i - ahead) % (ahead + 1)].synchronize()
-                if (sidx + 1) % cfg.period == 0 and args.updates != "none":
+                if (sidx + 1) % cfg.period == 0 and args.updates != "none" and args.policy != "lru":
                     for l, (lay, (d1, d2)) in enumerate(zip(layers, banks)):
                         if args.updates == "async":          # scores travel to the host behind the compute stream
-                            score_host[l].copy_(lay.score, non_blocking=True)
+                            score_host[l].copy_(rank_tensor(lay), non_blocking=True)
                             score_ev[l].record()
                             score_due[l] = True
                         else:
-                            score = lay.score.cpu().numpy()      # the one host read-back per period
+                            score = rank_tensor(lay).cpu().numpy()   # the one host read-back per period
                             for sl, ex in lay.select_resident(score):
                                 lay.set_resident(sl, ex, d1[ex], d2[ex])
                                 swaps += 1
@@ -226,6 +265,10 @@ def main():
         swaps = run(warmup, steps, True)
         dt = time.perf_counter() - t0
         active_log = (offs_log[:, 1:] > offs_log[:, :-1]).sum(dim=1).cpu().numpy().tolist()
+        hit_rate = None
+        if args.hit_rate:
+            oe = oe_log.cpu().numpy()
+            hit_rate = float(np.mean([(e2s_log[i][oe[i]] >= 0).mean() for i in range(steps)]))
 
     ms_per_step = dt / steps * 1e3
     value = T * L / (dt / steps)
@@ -287,7 +330,9 @@ def main():
               "step": "route+importance+permute+expert_ffn+combine over all layers"}
     if decode:
         config.update(update_period=cfg.period, experts_swapped=swaps, updates=args.updates, bank=args.bank,
-                      host_steps_ahead=max(1, args.max_ahead),
+                      host_steps_ahead=max(1, args.max_ahead), policy=args.policy,
+                      hit_rate=None if hit_rate is None else round(hit_rate, 4),
+                      bytes_loaded_per_step=round(swaps * 2.0 * cfg.d_model * cfg.d_ff * 2 / steps, 1),
                       spare_slots=args.spare_slots if args.updates == "async" else 0,
                       step="one decode step: route+importance+permute+expert_ffn+combine, plus score "
                            "read-back, policy and slot reloads every update_period steps")
