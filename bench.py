@@ -308,12 +308,14 @@ def main():
         import oracle
         Wr, W1, W2 = host0
         if not decode:
+            reps = 3 if args.workload != "c5" else 1
             t1 = time.perf_counter()
-            oracle.layer_forward(x_host, Wr, W1[:cfg.K], W2[:cfg.K], e2s0)
+            for _ in range(reps):
+                oracle.layer_forward(x_host, Wr, W1[:cfg.K], W2[:cfg.K], e2s0)
             tc = time.perf_counter() - t1
-            cpu = {"value": round(T / tc, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
-                   "kind": "oracle", "sample": f"one full layer (layer 0) of {cfg.name}, all {T} tokens, "
-                                               f"{tc:.2f}s wall"}
+            cpu = {"value": round(T * reps / tc, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
+                   "kind": "oracle", "sample": f"{reps} x one full layer (layer 0) of {cfg.name}, all {T} tokens "
+                                               f"each, {tc:.2f}s wall"}
         else:
             n = min(steps, 64)
             t1 = time.perf_counter()
