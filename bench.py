@@ -96,6 +96,7 @@ def main():
                          "per expert (the 'simple scheduling' ablation); static: the K experts of largest |E_i|, "
                          "never updated (magnitude pruning); lru: load-on-miss after every step, least recently "
                          "used slot evicted ('on demand' caching; --updates sync only)")
+    ap.add_argument("--period", type=int, default=None, help="c4 only: update period in steps (default 16)")
     ap.add_argument("--hit-rate", action="store_true",
                     help="c4 only: also log, per step, how many tokens found their own top-1 expert resident "
                          "(two small device copies per step inside the timed region)")
@@ -125,6 +126,8 @@ def main():
     dev = "cuda:0"
     cfg = wl.CONFIGS[args.workload]
     decode = cfg.period > 0
+    if decode and args.period:
+        cfg = cfg.scaled(period=max(1, args.period))
     steps = args.steps if args.steps is not None else (cfg.steps if decode else 50)
     warmup = args.warmup if args.warmup is not None else (16 if decode else 10)
     T = cfg.T
