@@ -43,18 +43,7 @@ constexpr int KPAD = 8;   // row-major token tile: LDS pitch (BKT+8)*2 B keeps b
 
 constexpr int XCDS = 8;   // MI355X: 8 accelerator dies, each with a private L2
 
-// Work item of workgroup `wg`.  A work item is (row tile, feature tile); the
-// row tiles of all slots form one list in slot order, ceil(len/bt) per slot.
-// Workgroups are dealt to the 8 XCDs round-robin by their linear id, so
-// workgroup wg runs on XCD wg % 8 as that die's (wg / 8)-th workgroup.  Die x
-// owns the x-th eighth of the row-tile list (a contiguous run, so it touches
-// few slots) and ALL feature tiles of those rows: activations are pulled
-// through exactly one L2, and a slot's weights through as few L2s as its rows
-// span.  On a die the row tile varies fastest, so workgroups that run together
-// share weight tiles and keep the die's activations L2-resident.
-// Returns false when the die has fewer items than wg / 8.
-// Outputs: slot, feature tile, first row m0, segment end m_end, and pm0 = the
-// padded row (segments re-based to multiples of 32) that m0 maps to.
+// Inclusive prefix sum over the 64 lanes of a wave.
 __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -64,62 +53,11 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
     return v;
 }
 
-// Every wave works the answer out on its own, slot k on lane k % 64 (64 slots
-// per pass): one vector load of the offsets, two wave scans, one ballot -- no
-// chain of dependent scalar loads at the head of every workgroup.
-__device__ __forceinline__ bool find_item(const int32_t* __restrict__ offsets, int nslots, int T, int bt,
-                                          int ftiles, int wg, int& slot, int& ftile, int& m0, int& m_end,
-                                          int& pm0) {
-    const int lane = threadIdx.x & 63;
-    // pass 1: number of row tiles over all slots
-    int total = 0;
-    for (int base = 0; base < nslots; base += 64) {
-        const int k = base + lane;
-        int tiles = 0;
-        if (k < nslots) {
-            int a = min(max(offsets[k], 0), T), b = max(min(max(offsets[k + 1], 0), T), a);   // clamps guard misuse
-            tiles = (b - a + bt - 1) / bt;
-        }
-        total += __shfl(wave_incl_scan(tiles, lane), 63);
-    }
-    const int die = wg % XCDS, j = wg / XCDS;
-    const int lo = (int)((long long)total * die / XCDS), hi = (int)((long long)total * (die + 1) / XCDS);
-    const int cnt = hi - lo;
-    if (cnt <= 0 || j >= cnt * ftiles) return false;
-    ftile = j / cnt;
-    const int mt = lo + j % cnt;                            // index into the global row-tile list
-    // pass 2: the slot that holds row tile mt, and the padded rows before it
-    int tiles_before = 0, pad_before = 0;
-    for (int base = 0; base < nslots; base += 64) {
-        const int k = base + lane;
-        int a = 0, b = 0, tiles = 0, pad = 0;
-        if (k < nslots) {
-            a = min(max(offsets[k], 0), T);
-            b = max(min(max(offsets[k + 1], 0), T), a);
-            tiles = (b - a + bt - 1) / bt;
-            pad = (b - a + 31) & ~31;
-        }
-        const int tin = wave_incl_scan(tiles, lane), pin = wave_incl_scan(pad, lane);
-        const int first = tiles_before + tin - tiles;       // first row tile of this lane's slot
-        const unsigned long long hit = __ballot(tiles > 0 && mt >= first && mt < first + tiles);
-        if (hit) {
-            const int src = __ffsll((long long)hit) - 1;
-            const int sa = __shfl(a, src), sb = __shfl(b, src);
-            const int sfirst = __shfl(first, src), spad = __shfl(pad_before + pin - pad, src);
-            slot = base + src;
-            m0 = sa + (mt - sfirst) * bt;
-            m_end = sb;
-            pm0 = spad + (mt - sfirst) * bt;
-            return true;
-        }
-        tiles_before += __shfl(tin, 63);
-        pad_before += __shfl(pin, 63);
-    }
-    return false;
-}
-
 // ---------------------------------------------------------------------------
-// Persistent form of the enumeration, for the tiled kernel.  The work items
+// Work enumeration of the tiled kernel.  A work item is (row tile, feature
+// tile); the row tiles of all slots form one list in slot order, ceil(len/bt)
+// per slot.  Workgroups are dealt to the 8 XCDs round-robin by their linear id,
+// so workgroup wg runs on XCD wg % 8.  The items
 // (row tile mt, feature tile ft) are numbered g = mt * ftiles + ft, and die x
 // owns the x-th eighth of that list: the dies' shares differ by at most one
 // item (a split by whole row tiles can leave one die with a fifth more work and
@@ -676,13 +614,13 @@ void launch_gemm(const uint16_t* X, const void* Wp, const int32_t* offsets, int 
                           (const uint4*)Wp, offsets, nslots, T, Y, R, N, fz);
 }
 
-constexpr int N_VARIANTS = 10;
+constexpr int N_VARIANTS = 11;
 
 template <bool FIRST>
 void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* offsets, int nslots,
                     uint16_t* Y, int R, int N, int T, const FuseArgs& fz, hipStream_t s, hipEvent_t e0,
                     hipEvent_t e1) {
-    if (R % 64 != 0 && v != 5 && v != 6 && v < 9) {   // d_model / d_ff are multiples of 32 by contract: 32-deep slices always fit
+    if (R % 64 != 0 && v != 5 && v != 6 && v != 9) {   // d_model / d_ff are multiples of 32 by contract: 32-deep slices always fit
         launch_gemm<1, 4, 4, 32, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1);
         return;
     }
@@ -694,6 +632,7 @@ void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* off
         case 4: launch_gemm<1, 1, 4, 64, 3, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  //  32 x 128
         case 7: launch_gemm<2, 4, 4, 64, 3, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  // 128 x 256, one wave per SIMD
         case 8: launch_gemm<1, 4, 8, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  // 128 x 256, 8 waves
+        case 10: launch_gemm<1, 8, 8, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break; // 256 x 256, 8 waves
         case 5: launch_small<4, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;   // 32 x 128, streaming
         case 6: launch_small<4, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;   // 32 x 32, reduction split 4 ways
         case 9: launch_small<4, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;   // 32 x 64, split 2
@@ -705,7 +644,8 @@ void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* off
 // built-in choice (a tuning aid; the indices are those of launch_variant).
 void pick_variants(const smoe_config& c, int T, int& v1, int& v2) {
     int per_slot = T / c.K;
-    if (per_slot >= 96) { v1 = 8; v2 = 1; }
+    if (per_slot >= 384) { v1 = 10; v2 = 1; }
+    else if (per_slot >= 96) { v1 = 8; v2 = 1; }
     else if (per_slot >= 48) { v1 = 2; v2 = 3; }
     else if (per_slot >= 8) { v1 = 4; v2 = 4; }
     else { v1 = 5; v2 = 6; }             // decode: a few tokens per slot, weight streaming
