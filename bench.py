@@ -96,6 +96,9 @@ def main():
                          "per expert (the 'simple scheduling' ablation); static: the K experts of largest |E_i|, "
                          "never updated (magnitude pruning); lru: load-on-miss after every step, least recently "
                          "used slot evicted ('on demand' caching; --updates sync only)")
+    ap.add_argument("--graph", action="store_true",
+                    help="c4 only: record one decode step of all layers into a HIP graph (one graph per value of "
+                         "the accumulate flag) and replay it per step; per-kernel events are not available then")
     ap.add_argument("--period", type=int, default=None, help="c4 only: update period in steps (default 16)")
     ap.add_argument("--hit-rate", action="store_true",
                     help="c4 only: also log, per step, how many tokens found their own top-1 expert resident "
@@ -201,6 +204,28 @@ def main():
         e2s_log = np.zeros((steps, cfg.E), np.int32)
         last_use = [np.zeros(cfg.K, np.int64) for _ in layers]    # lru: step of each slot's last use
 
+        graphs = {}
+        x_in = torch.empty(T, cfg.d_model, dtype=xs.dtype, device=dev)
+        if args.graph:
+            use_events = False
+            side = torch.cuda.Stream()
+            for acc in (0, 1):                                 # eager once (one-off set-up work), then capture
+                x = x_in
+                for lay in layers:
+                    x = fwd(lay)(x, T, accumulate=acc, residual=x)
+            torch.cuda.synchronize()
+            side.wait_stream(torch.cuda.current_stream())
+            for acc in (0, 1):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.stream(side):
+                    with torch.cuda.graph(g, stream=side):
+                        x = x_in
+                        for lay in layers:
+                            x = fwd(lay)(x, T, accumulate=acc, residual=x)
+                graphs[acc] = g
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+
         def rank_tensor(lay):
             return lay.count.to(torch.float32) if args.policy == "count" else lay.score
         n_samples = (steps + ev_stride - 1) // ev_stride
@@ -222,7 +247,10 @@ def main():
                             lay.update_begin(score_host[l].numpy())
                             score_due[l] = False
                 x = xs[sidx]
-                for l, lay in enumerate(layers):
+                if args.graph:
+                    x_in.copy_(x, non_blocking=True)
+                    graphs[0 if sidx % cfg.period == 0 else 1].replay()
+                for l, lay in enumerate(layers if not args.graph else []):
                     sampled = timed and i % ev_stride == 0 and l == (i // ev_stride) % L
                     if sampled and use_events:
                         b.smoe_set_profile_events(lay.handle, *evs[i])
@@ -335,7 +363,7 @@ def main():
               "step": "route+importance+permute+expert_ffn+combine over all layers"}
     if decode:
         config.update(update_period=cfg.period, experts_swapped=swaps, updates=args.updates, bank=args.bank,
-                      host_steps_ahead=max(1, args.max_ahead), policy=args.policy,
+                      host_steps_ahead=max(1, args.max_ahead), policy=args.policy, hip_graph=bool(args.graph),
                       hit_rate=None if hit_rate is None else round(hit_rate, 4),
                       bytes_loaded_per_step=round(swaps * 2.0 * cfg.d_model * cfg.d_ff * 2 / steps, 1),
                       spare_slots=args.spare_slots if args.updates == "async" else 0,
