@@ -106,3 +106,38 @@ def test_maps_and_policy_on_host():
     assert n == 3 and cs.tolist() == [0, 1, 2] and ce.tolist() == [1, 3, 5]
     assert b._lib.smoe_select_resident(h, None, cs.ctypes.data, ce.ctypes.data) == b.SMOE_EINVAL
     b.smoe_destroy(h)
+
+
+def test_header_is_plain_c():
+    """The boundary is a C ABI: the header must compile as C99 on its own."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    r = subprocess.run([gcc, "-x", "c", "-std=c99", "-fsyntax-only", "-Wall", "-Werror",
+                        os.path.join(ROOT, "include", "swapmoe.h")], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+
+
+def test_spare_slots_and_async_calls_without_a_gpu():
+    h = b.smoe_create(8, 2, 64, 256, 128, b.SMOE_BF16, spare_slots=2)
+    assert b.smoe_slot_weight_bytes(h) == (2 + 2) * 64 * 256 * 2
+    base = b.smoe_create(8, 2, 64, 256, 128, b.SMOE_BF16)
+    # staging area for host-bank loads: one expert (two matrices) per spare slot
+    assert b.smoe_workspace_bytes(h) - b.smoe_workspace_bytes(base) >= 2 * 2 * 64 * 256 * 2
+    assert _status(lambda: b.smoe_create(8, 2, 64, 256, 128, b.SMOE_BF16, spare_slots=9)) == b.SMOE_EINVAL
+    score = np.zeros(8, np.float32)
+    assert _status(b.smoe_update_begin, h, score) == b.SMOE_ESTATE          # not bound
+    assert _status(b.smoe_update_begin, base, score) == b.SMOE_ESTATE
+    assert b._lib.smoe_update_tick(h, FAKE, FAKE, None, None) == b.SMOE_ESTATE
+    assert b._lib.smoe_update_pending(None) == b.SMOE_EINVAL
+    assert b.smoe_update_pending(h) == 0
+    b.smoe_destroy(h); b.smoe_destroy(base)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in (r.stderr + r.stdout)
