@@ -326,7 +326,7 @@ def main():
             act = float(np.mean(active_log)) if active_log else float(cfg.K)
             bytes_launch = 2.0 * act * cfg.d_model * cfg.d_ff  # one weight matrix of every active slot
             achieved = bytes_launch / avg / 1e9
-            roof = {"bound": "hbm", "kernel": "small_gemm_bf16 (mean of the FFN's two launches)",
+            roof = {"bound": "hbm", "kernel": "dense_gemm_bf16 / small_gemm_bf16 (mean of the FFN's two launches)",
                     "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None,
                     "us_per_launch": round(avg * 1e6, 2), "us_gemm1": round(g1.mean() * 1e6, 2),

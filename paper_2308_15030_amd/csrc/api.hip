@@ -474,8 +474,8 @@ int smoe_forward(smoe_layer_t* L, const void* x, int T, const void* residual, vo
     rc = smoe_launch_rank_importance(L, orig_expert, orig_gate, xnorm, slot, T, count, gsum, score, accumulate,
                                      perm, inv_perm, offsets, s);
     if (rc) return rc;
-    rc = smoe_launch_ffn_bf16_fused(L, (const uint16_t*)x, perm, offsets, gate, (const uint16_t*)residual, T,
-                                    (uint16_t*)out, s);
+    rc = smoe_launch_ffn_bf16_fused(L, (const uint16_t*)x, slot, perm, offsets, gate, (const uint16_t*)residual,
+                                    T, (uint16_t*)out, s);
     L->prof_ev[0] = L->prof_ev[1] = L->prof_ev[2] = L->prof_ev[3] = nullptr;
     return rc;
 }

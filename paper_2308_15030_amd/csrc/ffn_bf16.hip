@@ -145,18 +145,24 @@ struct FuseArgs {
 // Fused combine on 4 consecutive outputs of one token.  The product is first
 // rounded to bf16 exactly as the unfused path stores y_perm, so both paths give
 // the same bits; then out = gate * y (+ residual) in fp32 with one final rounding.
-__device__ __forceinline__ void apply_gate(float& v0, float& v1, float& v2, float& v3, float g,
-                                           const uint16_t* res, bool fused) {
+__device__ __forceinline__ void apply_gate_v(float& v0, float& v1, float& v2, float& v3, float g, uint2 r,
+                                             bool has_res, bool fused) {
     if (!fused) return;
     v0 = smoe_bf16_to_f32(smoe_f32_to_bf16(v0)); v1 = smoe_bf16_to_f32(smoe_f32_to_bf16(v1));
     v2 = smoe_bf16_to_f32(smoe_f32_to_bf16(v2)); v3 = smoe_bf16_to_f32(smoe_f32_to_bf16(v3));
-    if (res) {
-        uint2 r = *(const uint2*)res;
+    if (has_res) {
         v0 = fmaf(g, v0, __uint_as_float(r.x << 16)); v1 = fmaf(g, v1, __uint_as_float(r.x & 0xFFFF0000u));
         v2 = fmaf(g, v2, __uint_as_float(r.y << 16)); v3 = fmaf(g, v3, __uint_as_float(r.y & 0xFFFF0000u));
     } else {
         v0 *= g; v1 *= g; v2 *= g; v3 *= g;
     }
+}
+
+__device__ __forceinline__ void apply_gate(float& v0, float& v1, float& v2, float& v3, float g,
+                                           const uint16_t* res, bool fused) {
+    uint2 r = make_uint2(0, 0);
+    if (fused && res) r = *(const uint2*)res;
+    apply_gate_v(v0, v1, v2, v3, g, r, res != nullptr, fused);
 }
 
 // One workgroup tile with NBF live token blocks.  Everything is compile-time
@@ -570,6 +576,127 @@ __global__ __launch_bounds__(NWV * 64) void small_gemm_bf16(
     }
 }
 
+// ---------------------------------------------------------------------------
+// One 32-token tile for the whole batch (T <= 32, the single-call path only).
+// With at most 32 tokens every slot's segment fits one MFMA token block, so
+// the sort is not needed to form the tiles: workgroup (slot, feature tile)
+// multiplies ALL T tokens, in token order, by the slot's weights and keeps the
+// columns of the tokens that were routed to the slot (an MFMA column depends on
+// its own token only, and the reduction order per element is that of
+// small_gemm_bf16, so the results are the same bits).  Nothing the workgroup
+// loads depends on another load: weights, token operands and the slot ids all
+// go out at once, instead of the chain offsets -> permutation -> rows.  A slot
+// nobody was routed to leaves after one group of weight loads.
+// The hidden activations are kept per slot: h[slot][feature/8][token] units of
+// 8 features (fragment order with the token index as the row).
+template <int NWV, int KSPLIT, bool FIRST>
+__global__ __launch_bounds__(NWV * 64) void dense_gemm_bf16(
+    const uint16_t* __restrict__ X, const uint4* __restrict__ Wp, const int32_t* __restrict__ slot_of,
+    int T, uint16_t* __restrict__ Y, int R, int N, const int32_t* __restrict__ phys,
+    const float* __restrict__ gate, const uint16_t* __restrict__ residual) {
+    constexpr int G = 8;                                   // reduction steps fetched together
+    constexpr int FBW = NWV / KSPLIT;                      // feature blocks per workgroup
+    __shared__ __align__(16) float red[KSPLIT > 1 ? (KSPLIT - 1) * FBW * 16 * 64 : 1];
+    const int nfb = N >> 5, nrb = R >> 4;
+    const int ftiles = (nfb + FBW - 1) / FBW;
+    const int slot = blockIdx.x / ftiles, ftile = blockIdx.x % ftiles;
+    // wave index as a scalar: MFMA loop bounds must be wave-uniform for the compiler too
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int fbi = wave / KSPLIT, part = wave % KSPLIT;
+    const int fb = ftile * FBW + fbi;
+    const bool fb_ok = fb < nfb;
+    const int per = (nrb + KSPLIT - 1) / KSPLIT;
+    const int kb_lo = min(part * per, nrb), kb_hi = min(kb_lo + per, nrb);
+    const int tok = lane & 31;
+    const uint4* wp = Wp + ((size_t)phys[slot] * nfb + min(fb, nfb - 1)) * nrb * 64 + lane;
+    uint4 wA[G], xA[G], wB[G], xB[G];
+    auto fetch_w = [&](uint4 (&w)[G], int g0) {
+#pragma unroll
+        for (int i = 0; i < G; ++i) w[i] = wp[(size_t)max(min(g0 + i, kb_hi - 1), 0) * 64];   // past the end: reloaded, not used
+    };
+    fetch_w(wA, kb_lo);                                    // on its way before anything else is known
+    const bool mine = tok < T && slot_of[min(tok, T - 1)] == slot;
+    const unsigned long long who = __ballot(mine);
+    if (who == 0) return;                                  // nothing routed to this slot (uniform over the workgroup)
+    // columns of other slots' tokens repeat the first routed token's operand: lanes that ask for
+    // the same address share one request, which keeps the token operand's traffic negligible
+    const int src_tok = mine ? tok : ((__ffsll((long long)who) - 1) & 31);
+    const uint4* xp;
+    size_t xstep;
+    if (FIRST) {                                           // row-major x, token order
+        xp = (const uint4*)(X + (size_t)src_tok * R + (lane >> 5) * 8);
+        xstep = 2;
+    } else {                                               // h[slot] in fragment order
+        xp = (const uint4*)X + ((size_t)slot * (R >> 3) + (lane >> 5)) * 32 + src_tok;
+        xstep = 2 * 32;
+    }
+    auto fetch_x = [&](uint4 (&xv)[G], int g0) {
+#pragma unroll
+        for (int i = 0; i < G; ++i) xv[i] = xp[(size_t)max(min(g0 + i, kb_hi - 1), 0) * xstep];
+    };
+    auto fetch = [&](uint4 (&w)[G], uint4 (&xv)[G], int g0) {
+        fetch_w(w, g0);
+        fetch_x(xv, g0);
+    };
+    fetch_x(xA, kb_lo);
+    float gmul = 1.f;
+    uint2 rres[4] = {};
+    if (!FIRST && mine && part == 0 && fb_ok) {            // asked for now, used after the loop
+        gmul = gate[tok];
+        if (residual) {
+            const uint16_t* rp = residual + (size_t)tok * N + fb * 32 + (lane >> 5) * 4;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) rres[g] = *(const uint2*)(rp + g * 8);
+        }
+    }
+    f32x16 acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    auto consume = [&](uint4 (&w)[G], uint4 (&xv)[G], int g0) {
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            const uint4 xz = g0 + i < kb_hi ? xv[i] : make_uint4(0, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(w[i]), as_frag(xz), acc, 0, 0, 0);
+        }
+    };
+    for (int g0 = kb_lo; g0 < kb_hi; g0 += 2 * G) {
+        fetch(wB, xB, g0 + G);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(wA, xA, g0);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(wA, xA, g0 + 2 * G);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(wB, xB, g0 + G);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (KSPLIT > 1) {
+        if (part > 0) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) red[(((part - 1) * FBW + fbi) * 16 + i) * 64 + lane] = acc[i];
+        }
+        __syncthreads();
+        if (part > 0) return;
+#pragma unroll
+        for (int w2 = 0; w2 < KSPLIT - 1; ++w2)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] += red[((w2 * FBW + fbi) * 16 + i) * 64 + lane];
+    }
+    if (!fb_ok || !mine) return;
+    // accumulator register i of lane l: feature 8*(i/4) + 4*(l/32) + i%4, token l%32
+    uint16_t* ydst = FIRST ? Y + (((size_t)slot * (N >> 3) + fb * 4) * 32 + tok) * 8 + (lane >> 5) * 4
+                           : Y + (size_t)tok * N + fb * 32 + (lane >> 5) * 4;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        float v0 = acc[4 * g], v1 = acc[4 * g + 1], v2 = acc[4 * g + 2], v3 = acc[4 * g + 3];
+        if (!FIRST) apply_gate_v(v0, v1, v2, v3, gmul, rres[g], residual != nullptr, true);
+        if (FIRST) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
+        uint2 o;
+        o.x = (uint32_t)smoe_f32_to_bf16(v0) | ((uint32_t)smoe_f32_to_bf16(v1) << 16);
+        o.y = (uint32_t)smoe_f32_to_bf16(v2) | ((uint32_t)smoe_f32_to_bf16(v3) << 16);
+        *(uint2*)(ydst + (FIRST ? g * 32 * 8 : g * 8)) = o;
+    }
+}
+
 template <int NWV, int KSPLIT, bool FIRST>
 void launch_small(const uint16_t* X, const void* Wp, const int32_t* offsets, int nslots, uint16_t* Y, int R,
                   int N, int T, const FuseArgs& fz, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
@@ -675,13 +802,23 @@ int smoe_launch_ffn_bf16(const smoe_layer* L, const uint16_t* x_perm, const int3
 
 // Fused form used by smoe_forward: the first product gathers its rows from x
 // through perm, the second scatters gate * y (+ residual) to out in token order.
-int smoe_launch_ffn_bf16_fused(const smoe_layer* L, const uint16_t* x, const int32_t* perm,
-                               const int32_t* offsets, const float* gate, const uint16_t* residual, int T,
-                               uint16_t* out, hipStream_t s) {
+int smoe_launch_ffn_bf16_fused(const smoe_layer* L, const uint16_t* x, const int32_t* slot_of,
+                               const int32_t* perm, const int32_t* offsets, const float* gate,
+                               const uint16_t* residual, int T, uint16_t* out, hipStream_t s) {
     const smoe_config& c = L->cfg;
     int v1, v2;
     pick_variants(c, T, v1, v2);
     uint16_t* h = (uint16_t*)L->d_hidden;
+    if (T <= 32 && v1 == 5 && v2 == 6) {      // the whole batch is one token block: no sorted tiles needed
+        const int nfb1 = c.d_ff >> 5, nfb2 = c.d_model >> 5;
+        smoe_launch_timed(dense_gemm_bf16<4, 1, true>, dim3(c.K * ((nfb1 + 3) / 4)), dim3(256), s, L->prof_ev[0],
+                          L->prof_ev[1], x, (const uint4*)L->slot_w1, slot_of, T, h, c.d_model, c.d_ff,
+                          (const int32_t*)L->d_phys, (const float*)nullptr, (const uint16_t*)nullptr);
+        smoe_launch_timed(dense_gemm_bf16<4, 4, false>, dim3(c.K * nfb2), dim3(256), s, L->prof_ev[2],
+                          L->prof_ev[3], (const uint16_t*)h, (const uint4*)L->slot_w2, slot_of, T, out, c.d_ff,
+                          c.d_model, (const int32_t*)L->d_phys, gate, residual);
+        return smoe_check_hip(hipGetLastError(), "smoe_forward: FFN launch");
+    }
     const FuseArgs gather{L->d_phys, perm, nullptr, nullptr}, scatter{L->d_phys, perm, gate, residual};
     launch_variant<true>(v1, x, L->slot_w1, offsets, c.K, h, c.d_model, c.d_ff, T, gather, s, L->prof_ev[0], L->prof_ev[1]);
     launch_variant<false>(v2, h, L->slot_w2, offsets, c.K, out, c.d_ff, c.d_model, T, scatter, s, L->prof_ev[2], L->prof_ev[3]);

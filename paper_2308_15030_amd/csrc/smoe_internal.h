@@ -79,9 +79,9 @@ int smoe_launch_rank_importance(const smoe_layer* L, const int32_t* orig_expert,
                                 const float* xnorm, const int32_t* slot, int T, int32_t* count, float* gsum,
                                 float* score, int accumulate, int32_t* perm, int32_t* inv_perm,
                                 int32_t* offsets, hipStream_t s);
-int smoe_launch_ffn_bf16_fused(const smoe_layer* L, const uint16_t* x, const int32_t* perm,
-                               const int32_t* offsets, const float* gate, const uint16_t* residual, int T,
-                               uint16_t* out, hipStream_t s);
+int smoe_launch_ffn_bf16_fused(const smoe_layer* L, const uint16_t* x, const int32_t* slot_of,
+                               const int32_t* perm, const int32_t* offsets, const float* gate,
+                               const uint16_t* residual, int T, uint16_t* out, hipStream_t s);
 int smoe_launch_importance(const smoe_layer* L, const int32_t* orig_expert, const float* orig_gate,
                            const float* xnorm, int T, int32_t* count, float* gsum, float* score,
                            int accumulate, hipStream_t s);

@@ -46,6 +46,9 @@ CASES = {
                          resident=[2, 0, 3, 1], router_scale=20.0),
     "renorm": dict(cfg=small_cfg("renorm", T=200), resident=[1, 2, 3], gate_mode=1, router_scale=20.0),
     "wide-E": dict(cfg=small_cfg("wide-E", E=200, K=20, T=1500, d_model=64, d_ff=96), router_scale=20.0),
+    # a decode-sized batch: at most 32 tokens, a few per slot (the single-call path multiplies the whole
+    # batch per slot and keeps the routed columns; the separate calls go through the sorted tiles)
+    "tiny-T": dict(cfg=small_cfg("tiny-T", E=16, K=5, T=27, d_model=128, d_ff=224), router_scale=20.0),
     "c2": dict(cfg=wl.CONFIGS["c2"]),
     "c3-layer0": dict(cfg=wl.CONFIGS["c3"], layer=0),
     "c3-layer5": dict(cfg=wl.CONFIGS["c3"], layer=5),
