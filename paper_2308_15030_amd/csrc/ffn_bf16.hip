@@ -136,7 +136,7 @@ __device__ __forceinline__ bf16x8 as_frag(uint4 v) {
 //   second product: row r is written to out[perm[r]] = gate[perm[r]] * y (+ residual[perm[r]]),
 //                   i.e. y = G(x)_i E_i(x) lands in token order (no y_perm).
 struct FuseArgs {
-    const int32_t* phys;      // virtual slot -> physical weight slot, [nslots] (always set)
+    const int32_t* phys;      // virtual slot -> physical weight slot, [nslots]; NULL = identity (no spare slots)
     const int32_t* perm;
     const float* gate;
     const uint16_t* residual;
@@ -411,7 +411,7 @@ __global__ __launch_bounds__(NW * 64, OCC) void grouped_gemm_bf16(
         const int mt = (int)(g / ftiles), ftile = (int)(g % ftiles);
         int slot, m0, m_end, pm0;
         row_tile_at(map, nslots, BT, mt, slot, m0, m_end, pm0);
-        slot = __builtin_amdgcn_readfirstlane(fz.phys[slot]);   // from here on: where the weights live
+        if (fz.phys) slot = __builtin_amdgcn_readfirstlane(fz.phys[slot]);   // from here on: where the weights live
         const int nbf = min(MAXB, (m_end - m0 + 31) >> 5);    // token blocks that hold real rows
         TileSwitch<AF, MAXB, MAXB, NW, BKT, PD, !FIRST, FIRST, FIRST>::go(nbf, X, Wp, Y, R, N, slot, m0, m_end,
                                                                          pm0, ftile, xs, fz);
@@ -455,7 +455,7 @@ __global__ __launch_bounds__(NWV * 64) void small_gemm_bf16(
     const bool fb_ok = fb < nfb;
     const int per = (nrb + KSPLIT - 1) / KSPLIT;
     const int kb_lo = min(part * per, nrb), kb_hi = min(kb_lo + per, nrb);
-    const uint4* wp = Wp + ((size_t)fz.phys[slot] * nfb + min(fb, nfb - 1)) * nrb * 64 + lane;
+    const uint4* wp = Wp + ((size_t)(fz.phys ? fz.phys[slot] : slot) * nfb + min(fb, nfb - 1)) * nrb * 64 + lane;
 
     uint4 wA[G], xA[G], wB[G], xB[G];
     auto fetch_w = [&](uint4 (&w)[G], int g0) {
@@ -608,7 +608,7 @@ __global__ __launch_bounds__(NWV * 64) void dense_gemm_bf16(
     const int per = (nrb + KSPLIT - 1) / KSPLIT;
     const int kb_lo = min(part * per, nrb), kb_hi = min(kb_lo + per, nrb);
     const int tok = lane & 31;
-    const uint4* wp = Wp + ((size_t)phys[slot] * nfb + min(fb, nfb - 1)) * nrb * 64 + lane;
+    const uint4* wp = Wp + ((size_t)(phys ? phys[slot] : slot) * nfb + min(fb, nfb - 1)) * nrb * 64 + lane;
     uint4 wA[G], xA[G], wB[G], xB[G];
     auto fetch_w = [&](uint4 (&w)[G], int g0) {
 #pragma unroll
@@ -794,7 +794,8 @@ int smoe_launch_ffn_bf16(const smoe_layer* L, const uint16_t* x_perm, const int3
     int v1, v2;
     pick_variants(c, T, v1, v2);
     uint16_t* h = (uint16_t*)L->d_hidden;
-    const FuseArgs none{L->d_phys, nullptr, nullptr, nullptr};
+    const int32_t* phys = L->cfg.spare_slots > 0 ? L->d_phys : nullptr;   // identity without spare slots
+    const FuseArgs none{phys, nullptr, nullptr, nullptr};
     launch_variant<true>(v1, x_perm, L->slot_w1, offsets, c.K, h, c.d_model, c.d_ff, T, none, s, L->prof_ev[0], L->prof_ev[1]);
     launch_variant<false>(v2, h, L->slot_w2, offsets, c.K, y_perm, c.d_ff, c.d_model, T, none, s, L->prof_ev[2], L->prof_ev[3]);
     return smoe_check_hip(hipGetLastError(), "smoe_expert_ffn launch");
@@ -809,17 +810,18 @@ int smoe_launch_ffn_bf16_fused(const smoe_layer* L, const uint16_t* x, const int
     int v1, v2;
     pick_variants(c, T, v1, v2);
     uint16_t* h = (uint16_t*)L->d_hidden;
+    const int32_t* phys = L->cfg.spare_slots > 0 ? L->d_phys : nullptr;   // identity without spare slots
     if (T <= 32 && v1 == 5 && v2 == 6) {      // the whole batch is one token block: no sorted tiles needed
         const int nfb1 = c.d_ff >> 5, nfb2 = c.d_model >> 5;
         smoe_launch_timed(dense_gemm_bf16<4, 1, true>, dim3(c.K * ((nfb1 + 3) / 4)), dim3(256), s, L->prof_ev[0],
                           L->prof_ev[1], x, (const uint4*)L->slot_w1, slot_of, T, h, c.d_model, c.d_ff,
-                          (const int32_t*)L->d_phys, (const float*)nullptr, (const uint16_t*)nullptr);
+                          phys, (const float*)nullptr, (const uint16_t*)nullptr);
         smoe_launch_timed(dense_gemm_bf16<4, 4, false>, dim3(c.K * nfb2), dim3(256), s, L->prof_ev[2],
                           L->prof_ev[3], (const uint16_t*)h, (const uint4*)L->slot_w2, slot_of, T, out, c.d_ff,
-                          c.d_model, (const int32_t*)L->d_phys, gate, residual);
+                          c.d_model, phys, gate, residual);
         return smoe_check_hip(hipGetLastError(), "smoe_forward: FFN launch");
     }
-    const FuseArgs gather{L->d_phys, perm, nullptr, nullptr}, scatter{L->d_phys, perm, gate, residual};
+    const FuseArgs gather{phys, perm, nullptr, nullptr}, scatter{phys, perm, gate, residual};
     launch_variant<true>(v1, x, L->slot_w1, offsets, c.K, h, c.d_model, c.d_ff, T, gather, s, L->prof_ev[0], L->prof_ev[1]);
     launch_variant<false>(v2, h, L->slot_w2, offsets, c.K, out, c.d_ff, c.d_model, T, scatter, s, L->prof_ev[2], L->prof_ev[3]);
     return smoe_check_hip(hipGetLastError(), "smoe_forward: FFN launch");
