@@ -304,43 +304,68 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
     sqp[(wave * 2 + (lane >> 5)) * RT + (lane & 31)] = sq;
     __syncthreads();
 
-    // epilogue: the first 256 threads, lanes 8*st .. 8*st+7 own token st
-    if (tid < 256) {
-    const int st = tid >> 3, sub = tid & 7;
-    const int tok = t0 + st;
+    // epilogue: lane l of wave w owns token l%32 and the experts j, j + 2*NWR, ... with
+    // j = 2w + l/32, so a wave's LDS reads walk consecutive tokens (no bank conflicts) and
+    // every thread takes part; the per-token results meet through small LDS tables.
+    constexpr int EG = 2 * NWR;                   // expert groups per token
+    constexpr int EPL = EP / EG;                  // experts per lane
+    __shared__ float s_best[NWR][RT], s_rbest[NWR][RT], s_z[NWR][RT], s_zr[NWR][RT];
+    __shared__ int32_t s_bi[NWR][RT], s_rbi[NWR][RT];
+    const int st = lane & 31, half = lane >> 5;
+    float v[EPL];
     float best = -INFINITY, rbest = -INFINITY;
     int bi = 0x7fffffff, rbi = 0x7fffffff;
-    for (int e = sub; e < E; e += 8) {
-        float v = part[e * RTP + st];
 #pragma unroll
-        for (int w = 1; w < NWR; ++w) v += part[(w * EP + e) * RTP + st];     // fixed order
-        part[e * RTP + st] = v;                   // wave 0's slot now holds the full logit
-        if (v > best) { best = v; bi = e; }
-        if (s_e2s[e] >= 0 && v > rbest) { rbest = v; rbi = e; }
+    for (int i = 0; i < EPL; ++i) {
+        const int e = wave * 2 + half + EG * i;
+        float sum = part[e * RTP + st];
+#pragma unroll
+        for (int w = 1; w < NWR; ++w) sum += part[(w * EP + e) * RTP + st];   // fixed order
+        v[i] = sum;
+        if (e < E) {                              // ascending e: the lowest index wins a tie
+            if (sum > best) { best = sum; bi = e; }
+            if (s_e2s[e] >= 0 && sum > rbest) { rbest = sum; rbi = e; }
+        }
     }
-#pragma unroll
-    for (int m = 1; m < 8; m <<= 1) {
-        float ov = __shfl_xor(best, m); int oi = __shfl_xor(bi, m);
+    {
+        float ov = __shfl_xor(best, 32); int oi = __shfl_xor(bi, 32);
         if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
-        float rv = __shfl_xor(rbest, m); int ri = __shfl_xor(rbi, m);
+        float rv = __shfl_xor(rbest, 32); int ri = __shfl_xor(rbi, 32);
+        if (rv > rbest || (rv == rbest && ri < rbi)) { rbest = rv; rbi = ri; }
+    }
+    if (half == 0) { s_best[wave][st] = best; s_bi[wave][st] = bi; s_rbest[wave][st] = rbest; s_rbi[wave][st] = rbi; }
+    __syncthreads();
+    best = s_best[0][st]; bi = s_bi[0][st]; rbest = s_rbest[0][st]; rbi = s_rbi[0][st];
+#pragma unroll
+    for (int w = 1; w < NWR; ++w) {
+        const float ov = s_best[w][st]; const int oi = s_bi[w][st];
+        if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+        const float rv = s_rbest[w][st]; const int ri = s_rbi[w][st];
         if (rv > rbest || (rv == rbest && ri < rbi)) { rbest = rv; rbi = ri; }
     }
     float z = 0.f, zr = 0.f;
-    for (int e = sub; e < E; e += 8) {
-        float p = expf(part[e * RTP + st] - best);
-        z += p;
-        if (s_e2s[e] >= 0) zr += p;
-    }
 #pragma unroll
-    for (int m = 1; m < 8; m <<= 1) {
-        z += __shfl_xor(z, m);
-        zr += __shfl_xor(zr, m);
+    for (int i = 0; i < EPL; ++i) {
+        const int e = wave * 2 + half + EG * i;
+        if (e < E) {
+            const float p = expf(v[i] - best);
+            z += p;
+            if (s_e2s[e] >= 0) zr += p;
+        }
     }
-    if (sub == 0 && tok < T) {
+    z += __shfl_xor(z, 32);
+    zr += __shfl_xor(zr, 32);
+    if (half == 0) { s_z[wave][st] = z; s_zr[wave][st] = zr; }
+    __syncthreads();
+    if (tid < RT && t0 + tid < T) {               // st == tid: one lane per token finishes
+        const int tok = t0 + tid;
+        z = s_z[0][st]; zr = s_zr[0][st];
+#pragma unroll
+        for (int w = 1; w < NWR; ++w) { z += s_z[w][st]; zr += s_zr[w][st]; }
         float ss = 0.f;
 #pragma unroll
         for (int q = 0; q < 2 * NWR; ++q) ss += sqp[q * RT + st];
-        float ps = expf(rbest - best);
+        const float ps = expf(rbest - best);
         orig_expert[tok] = bi;
         orig_gate[tok] = 1.0f / z;
         const int sv = rbi < EP ? s_e2s[rbi] : 0;    // rbi is always valid once every slot is set
@@ -348,7 +373,6 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
         s_slot[st] = sv;
         gate[tok] = gate_mode == SMOE_GATE_RENORM ? ps / zr : ps / z;
         xnorm[tok] = sqrtf(ss);
-    }
     }
     if (hist32) {                                 // tokens per slot in this block, for the fused sort
         __syncthreads();

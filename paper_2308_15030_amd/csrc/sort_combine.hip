@@ -22,28 +22,32 @@ namespace {
 // is bit-reproducible (no atomics, no dependence on scheduling).
 constexpr int IMP_THREADS = 256;
 
-__global__ __launch_bounds__(IMP_THREADS) void importance_kernel(
-    const int32_t* __restrict__ orig_expert, const float* __restrict__ orig_gate,
-    const float* __restrict__ xnorm, const float* __restrict__ expert_norm, int T,
-    int32_t* __restrict__ count, float* __restrict__ gsum, float* __restrict__ score, int accumulate) {
-    __shared__ int32_t s_c[IMP_THREADS];
-    __shared__ float s_g[IMP_THREADS], s_r[IMP_THREADS];
-    const int e = blockIdx.x, tid = threadIdx.x;
-    int c = 0;
-    float g = 0.f, r = 0.f;
+// Thread tid's share of expert e's three sums: tokens tid, tid + 256, ... added
+// in that order.  The loads of IMP_UNROLL tokens are issued together, the adds
+// stay sequential, so the result does not depend on the unrolling.
+constexpr int IMP_UNROLL = 8;
+
+__device__ __forceinline__ void importance_share(const int32_t* __restrict__ orig_expert,
+                                                 const float* __restrict__ orig_gate,
+                                                 const float* __restrict__ xnorm, int T, int e, int tid,
+                                                 int& c, float& g, float& r) {
+    c = 0; g = 0.f; r = 0.f;
     int t = tid;
-    for (; t + 3 * IMP_THREADS < T; t += 4 * IMP_THREADS) {      // four independent loads in flight
-        int e0 = orig_expert[t], e1 = orig_expert[t + IMP_THREADS], e2 = orig_expert[t + 2 * IMP_THREADS],
-            e3 = orig_expert[t + 3 * IMP_THREADS];
-        float g0 = orig_gate[t], g1 = orig_gate[t + IMP_THREADS], g2 = orig_gate[t + 2 * IMP_THREADS],
-              g3 = orig_gate[t + 3 * IMP_THREADS];
-        float x0 = xnorm[t], x1 = xnorm[t + IMP_THREADS], x2 = xnorm[t + 2 * IMP_THREADS],
-              x3 = xnorm[t + 3 * IMP_THREADS];
-        c += (e0 == e) + (e1 == e) + (e2 == e) + (e3 == e);
-        g += e0 == e ? g0 : 0.f; r += e0 == e ? x0 * g0 : 0.f;
-        g += e1 == e ? g1 : 0.f; r += e1 == e ? x1 * g1 : 0.f;
-        g += e2 == e ? g2 : 0.f; r += e2 == e ? x2 * g2 : 0.f;
-        g += e3 == e ? g3 : 0.f; r += e3 == e ? x3 * g3 : 0.f;
+    for (; t + (IMP_UNROLL - 1) * IMP_THREADS < T; t += IMP_UNROLL * IMP_THREADS) {
+        int ev[IMP_UNROLL];
+        float gv[IMP_UNROLL], xv[IMP_UNROLL];
+#pragma unroll
+        for (int i = 0; i < IMP_UNROLL; ++i) {
+            ev[i] = orig_expert[t + i * IMP_THREADS];
+            gv[i] = orig_gate[t + i * IMP_THREADS];
+            xv[i] = xnorm[t + i * IMP_THREADS];
+        }
+#pragma unroll
+        for (int i = 0; i < IMP_UNROLL; ++i) {
+            c += ev[i] == e;
+            g += ev[i] == e ? gv[i] : 0.f;
+            r += ev[i] == e ? xv[i] * gv[i] : 0.f;
+        }
     }
     for (; t < T; t += IMP_THREADS) {
         int e0 = orig_expert[t];
@@ -52,6 +56,18 @@ __global__ __launch_bounds__(IMP_THREADS) void importance_kernel(
         g += e0 == e ? g0 : 0.f;
         r += e0 == e ? x0 * g0 : 0.f;
     }
+}
+
+__global__ __launch_bounds__(IMP_THREADS) void importance_kernel(
+    const int32_t* __restrict__ orig_expert, const float* __restrict__ orig_gate,
+    const float* __restrict__ xnorm, const float* __restrict__ expert_norm, int T,
+    int32_t* __restrict__ count, float* __restrict__ gsum, float* __restrict__ score, int accumulate) {
+    __shared__ int32_t s_c[IMP_THREADS];
+    __shared__ float s_g[IMP_THREADS], s_r[IMP_THREADS];
+    const int e = blockIdx.x, tid = threadIdx.x;
+    int c;
+    float g, r;
+    importance_share(orig_expert, orig_gate, xnorm, T, e, tid, c, g, r);
     s_c[tid] = c; s_g[tid] = g; s_r[tid] = r;
     __syncthreads();
     for (int w = IMP_THREADS / 2; w > 0; w >>= 1) {
@@ -176,15 +192,9 @@ __global__ __launch_bounds__(SB) void rank_importance_kernel(
         float* s_g = (float*)(sm + IMP_THREADS);
         float* s_r = (float*)(sm + 2 * IMP_THREADS);
         if (tid < IMP_THREADS) {
-            int c = 0;
-            float g = 0.f, r = 0.f;
-            for (int t = tid; t < T; t += IMP_THREADS) {
-                const int e0 = orig_expert[t];
-                const float g0 = orig_gate[t], x0 = xnorm[t];
-                c += e0 == e;
-                g += e0 == e ? g0 : 0.f;
-                r += e0 == e ? x0 * g0 : 0.f;
-            }
+            int c;
+            float g, r;
+            importance_share(orig_expert, orig_gate, xnorm, T, e, tid, c, g, r);
             s_c[tid] = c; s_g[tid] = g; s_r[tid] = r;
         }
         __syncthreads();
