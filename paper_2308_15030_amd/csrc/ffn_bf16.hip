@@ -813,7 +813,7 @@ int smoe_launch_ffn_bf16_fused(const smoe_layer* L, const uint16_t* x, const int
     const int32_t* phys = L->cfg.spare_slots > 0 ? L->d_phys : nullptr;   // identity without spare slots
     if (T <= 32 && v1 == 5 && v2 == 6) {      // the whole batch is one token block: no sorted tiles needed
         const int nfb1 = c.d_ff >> 5, nfb2 = c.d_model >> 5;
-        smoe_launch_timed(dense_gemm_bf16<4, 1, true>, dim3(c.K * ((nfb1 + 3) / 4)), dim3(256), s, L->prof_ev[0],
+        smoe_launch_timed(dense_gemm_bf16<6, 1, true>, dim3(c.K * ((nfb1 + 5) / 6)), dim3(384), s, L->prof_ev[0],
                           L->prof_ev[1], x, (const uint4*)L->slot_w1, slot_of, T, h, c.d_model, c.d_ff,
                           phys, (const float*)nullptr, (const uint16_t*)nullptr);
         smoe_launch_timed(dense_gemm_bf16<4, 4, false>, dim3(c.K * nfb2), dim3(256), s, L->prof_ev[2],
