@@ -200,10 +200,13 @@ int smoe_set_resident(smoe_layer_t* L, int slot, int expert, const void* w1_src,
             return smoe_fail(SMOE_ESTATE, "smoe_set_resident: slot %d / expert %d has an asynchronous load in flight",
                              st.slot, st.expert);
     int old = L->slot_to_expert[slot];
-    int rc = smoe_launch_pack_slot(L, L->phys[slot], w1_src, w2_src, s);
+    int map_done = 0;
+    int rc = smoe_launch_pack_slot(L, L->phys[slot], w1_src, w2_src, s, slot, expert, old, &map_done);
     if (rc) return rc;
-    rc = smoe_launch_set_map(L, slot, expert, old, L->phys[slot], s);
-    if (rc) return rc;
+    if (!map_done) {
+        rc = smoe_launch_set_map(L, slot, expert, old, L->phys[slot], s);
+        if (rc) return rc;
+    }
     if (old >= 0) L->expert_to_slot[old] = -1; else L->slots_set += 1;
     L->slot_to_expert[slot] = expert;
     L->expert_to_slot[expert] = slot;
@@ -469,11 +472,17 @@ int smoe_forward(smoe_layer_t* L, const void* x, int T, const void* residual, vo
         if (rc) return rc;
         L->router_split_done = true;
     }
-    rc = smoe_launch_route(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, L->d_hist32, s);
-    if (rc) return rc;
-    rc = smoe_launch_rank_importance(L, orig_expert, orig_gate, xnorm, slot, T, count, gsum, score, accumulate,
-                                     perm, inv_perm, offsets, s);
-    if (rc) return rc;
+    if (T <= 32) {   // decode-sized batch: the router's one workgroup ranks and accumulates as well
+        rc = smoe_launch_route_rank_small(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, count, gsum, score,
+                                          accumulate, perm, inv_perm, offsets, s);
+        if (rc) return rc;
+    } else {
+        rc = smoe_launch_route(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, L->d_hist32, s);
+        if (rc) return rc;
+        rc = smoe_launch_rank_importance(L, orig_expert, orig_gate, xnorm, slot, T, count, gsum, score, accumulate,
+                                         perm, inv_perm, offsets, s);
+        if (rc) return rc;
+    }
     rc = smoe_launch_ffn_bf16_fused(L, (const uint16_t*)x, slot, perm, offsets, gate, (const uint16_t*)residual,
                                     T, (uint16_t*)out, s);
     L->prof_ev[0] = L->prof_ev[1] = L->prof_ev[2] = L->prof_ev[3] = nullptr;

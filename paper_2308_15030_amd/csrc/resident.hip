@@ -34,9 +34,8 @@ __global__ void set_map_kernel(int32_t* e2s, int32_t* s2e, int32_t* phys, int sl
 // One thread builds one 16-byte packed unit: 8 consecutive reduction rows of
 // one feature column.  Within a wave the 32 feature columns are adjacent, so
 // each of the 8 row reads is a 64-byte run and the write is a full 1-KiB block.
-__global__ __launch_bounds__(256) void pack_bf16_kernel(const uint16_t* __restrict__ src, int R, int N,
-                                                        uint4* __restrict__ dst) {
-    size_t unit = (size_t)blockIdx.x * 256 + threadIdx.x;        // = (nb * R/16 + rb) * 64 + lane
+__device__ __forceinline__ void pack_unit(const uint16_t* __restrict__ src, int R, int N,
+                                          uint4* __restrict__ dst, size_t unit) {
     size_t total = (size_t)(N / 32) * (R / 16) * 64;
     if (unit >= total) return;
     int lane = (int)(unit & 63);
@@ -52,6 +51,26 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint16_t* __restri
         w[i] = lo | (hi << 16);
     }
     dst[unit] = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// Loads one expert into a physical slot in a single launch: blocks [0, nblk)
+// pack W1 [d_model, d_ff], blocks [nblk, 2 nblk) pack W2 [d_ff, d_model] (both
+// have d_model * d_ff / 8 units); with map_slot >= 0 the first thread also
+// switches the maps.  The maps are read only by later launches of the stream, which
+// start after this whole launch (weights included) has completed.
+__global__ __launch_bounds__(256) void pack_bf16_kernel(const uint16_t* __restrict__ w1, const uint16_t* __restrict__ w2,
+                                                        int d_model, int d_ff, uint4* __restrict__ dst1,
+                                                        uint4* __restrict__ dst2, int nblk, int32_t* e2s,
+                                                        int32_t* s2e, int32_t* phys, int map_slot, int expert,
+                                                        int old_expert, int p) {
+    if ((int)blockIdx.x < nblk) pack_unit(w1, d_model, d_ff, dst1, (size_t)blockIdx.x * 256 + threadIdx.x);
+    else pack_unit(w2, d_ff, d_model, dst2, (size_t)(blockIdx.x - nblk) * 256 + threadIdx.x);
+    if (map_slot >= 0 && blockIdx.x == 0 && threadIdx.x == 0) {
+        if (old_expert >= 0) e2s[old_expert] = -1;
+        e2s[expert] = map_slot;
+        s2e[map_slot] = expert;
+        phys[map_slot] = p;
+    }
 }
 
 __global__ __launch_bounds__(256) void copy16_kernel(const uint4* __restrict__ src, size_t n16,
@@ -114,18 +133,22 @@ int smoe_launch_clear_maps(const smoe_layer* L, hipStream_t s) {
     return smoe_check_hip(hipGetLastError(), "smoe_set_resident: map reset");
 }
 
-int smoe_launch_pack_slot(const smoe_layer* L, int slot, const void* w1_src, const void* w2_src, hipStream_t s) {
+// map_slot >= 0: the launch that loads the weights also switches the maps (bf16 layers; fp32
+// layers take the separate map launch).  Returns 1 in *map_done when it did.
+int smoe_launch_pack_slot(const smoe_layer* L, int slot, const void* w1_src, const void* w2_src, hipStream_t s,
+                          int map_slot, int expert, int old_expert, int* map_done) {
     const smoe_config& c = L->cfg;
     const size_t per = (size_t)c.d_model * c.d_ff;               // elements per matrix
+    if (map_done) *map_done = 0;
     if (c.dtype == SMOE_BF16) {
         size_t units = per / 8;
-        dim3 grid((unsigned)((units + 255) / 256));
+        const int nblk = (int)((units + 255) / 256);
         uint4* d1 = (uint4*)((uint16_t*)L->slot_w1 + (size_t)slot * per);
         uint4* d2 = (uint4*)((uint16_t*)L->slot_w2 + (size_t)slot * per);
-        hipLaunchKernelGGL(pack_bf16_kernel, grid, dim3(256), 0, s, (const uint16_t*)w1_src, c.d_model,
-                           c.d_ff, d1);
-        hipLaunchKernelGGL(pack_bf16_kernel, grid, dim3(256), 0, s, (const uint16_t*)w2_src, c.d_ff,
-                           c.d_model, d2);
+        hipLaunchKernelGGL(pack_bf16_kernel, dim3(2 * nblk), dim3(256), 0, s, (const uint16_t*)w1_src,
+                           (const uint16_t*)w2_src, c.d_model, c.d_ff, d1, d2, nblk, L->d_expert_to_slot,
+                           L->d_slot_to_expert, L->d_phys, map_slot, expert, old_expert, slot);
+        if (map_done && map_slot >= 0) *map_done = 1;
     } else {
         size_t n16 = per * 4 / 16;
         dim3 grid((unsigned)((n16 + 255) / 256));

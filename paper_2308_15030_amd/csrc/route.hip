@@ -222,13 +222,29 @@ __global__ __launch_bounds__(256) void split_router_kernel(const float* __restri
 constexpr int RT = 32;            // tokens per workgroup
 constexpr int RTP = RT + 1;       // padded row of the partial-logit tile
 
+// A batch of at most RT tokens is one workgroup, which then holds every token's
+// result and can finish the step's ranking (smoe_permute's index part) and the
+// importance sums (Eq. 1) itself: the single-call path saves a launch.
+// perm == nullptr: plain router.
+struct TailArgs {
+    const float* expert_norm;
+    int32_t* count;
+    float* gsum;
+    float* score;
+    int accumulate;
+    int32_t* perm;
+    int32_t* inv_perm;
+    int32_t* offsets;
+};
+
 // NEB = 32-expert blocks, NWR = waves per workgroup (each takes 1/NWR of d_model).
 template <int NEB, int NWR>
 __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
     const uint16_t* __restrict__ x, const uint4* __restrict__ Wsplit, const int32_t* __restrict__ e2s,
     int T, int d, int E, int gate_mode,
     int32_t* __restrict__ orig_expert, float* __restrict__ orig_gate, int32_t* __restrict__ slot,
-    float* __restrict__ gate, float* __restrict__ xnorm, int32_t* __restrict__ hist32, int K) {
+    float* __restrict__ gate, float* __restrict__ xnorm, int32_t* __restrict__ hist32, int K,
+    const TailArgs tail) {
     extern __shared__ __align__(16) float smem[];
     __shared__ int32_t s_slot[RT];
     constexpr int EP = NEB * 32;
@@ -311,6 +327,8 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
     constexpr int EPL = EP / EG;                  // experts per lane
     __shared__ float s_best[NWR][RT], s_rbest[NWR][RT], s_z[NWR][RT], s_zr[NWR][RT];
     __shared__ int32_t s_bi[NWR][RT], s_rbi[NWR][RT];
+    __shared__ int32_t s_oe[RT];
+    __shared__ float s_og[RT], s_xn[RT];
     const int st = lane & 31, half = lane >> 5;
     float v[EPL];
     float best = -INFINITY, rbest = -INFINITY;
@@ -372,7 +390,9 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
         slot[tok] = sv;
         s_slot[st] = sv;
         gate[tok] = gate_mode == SMOE_GATE_RENORM ? ps / zr : ps / z;
-        xnorm[tok] = sqrtf(ss);
+        const float xn = sqrtf(ss);
+        xnorm[tok] = xn;
+        s_oe[st] = bi; s_og[st] = 1.0f / z; s_xn[st] = xn;      // for the single-workgroup tail
     }
     if (hist32) {                                 // tokens per slot in this block, for the fused sort
         __syncthreads();
@@ -383,11 +403,80 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
             hist32[(size_t)blockIdx.x * K + k] = c;
         }
     }
+    if (!tail.perm) return;
+    // ---- single-workgroup tail (T <= RT, one workgroup): ranking and importance
+    __shared__ int32_t s_cnt[256], s_off[256];
+    for (int k = tid; k < 256; k += THREADS) s_cnt[k] = 0;
+    __syncthreads();
+    // stable rank by slot (wave 0): position = slot offset + earlier tokens of the same slot,
+    // exactly the order of the sorting kernels
+    int my = 0, rank_in_slot = 0;
+    const bool live = wave == 0 && lane < T;
+    if (wave == 0) {
+        my = live ? s_slot[lane & 31] : 0;
+        unsigned long long peers = __ballot(live);
+        for (int bit = 0; (1 << bit) < K; ++bit) {
+            const unsigned long long b = __ballot(live && ((my >> bit) & 1));
+            peers &= ((my >> bit) & 1) ? b : ~b;
+        }
+        rank_in_slot = __popcll(peers & ((1ull << lane) - 1ull));
+        if (live && rank_in_slot == 0) s_cnt[my] = __popcll(peers);
+    }
+    __syncthreads();
+    if (wave == 0) {                              // exclusive scan of the slot counts, 64 slots at a time
+        int before = 0;
+        for (int base = 0; base < K; base += 64) {
+            const int k = base + lane;
+            const int c = k < K ? s_cnt[k] : 0;
+            int incl = c;
+#pragma unroll
+            for (int dd = 1; dd < 64; dd <<= 1) {
+                const int o = __shfl_up(incl, dd);
+                if (lane >= dd) incl += o;
+            }
+            if (k < K) { s_off[k] = before + incl - c; tail.offsets[k] = before + incl - c; }
+            before += __shfl(incl, 63);
+        }
+        if (lane == 0) tail.offsets[K] = before;
+    }
+    __syncthreads();
+    if (live) {
+        const int pos = s_off[my] + rank_in_slot;
+        tail.perm[pos] = lane;
+        tail.inv_perm[lane] = pos;
+    }
+    // importance: thread e sums expert e's tokens (those whose own top-1 it is).  The tokens sit
+    // in leaves 0..31 of the separate call's 256-leaf summation tree and its other leaves are
+    // zero, so evaluating that tree's last five levels in registers gives the same bits.
+    if (tid < E) {
+        const int e = tid;
+        const float en = tail.expert_norm[e];                 // asked for before the arithmetic
+        int c0 = 0;
+        float g0 = 0.f, r0 = 0.f;
+        if (tail.accumulate) { c0 = tail.count[e]; g0 = tail.gsum[e]; r0 = tail.score[e]; }
+        int c = 0;
+        float g[RT], r[RT];
+#pragma unroll
+        for (int t = 0; t < RT; ++t) {                         // same address in every lane: LDS broadcasts
+            const bool hit = t < T && s_oe[t] == e;
+            c += hit;
+            g[t] = hit ? s_og[t] : 0.f;
+            r[t] = hit ? s_xn[t] * s_og[t] : 0.f;
+        }
+#pragma unroll
+        for (int w = RT / 2; w > 0; w >>= 1)
+#pragma unroll
+            for (int i = 0; i < w; ++i) { g[i] += g[i + w]; r[i] += r[i + w]; }
+        const float sc = en * r[0];
+        tail.count[e] = c0 + c;
+        tail.gsum[e] = tail.accumulate ? g0 + g[0] : g[0];
+        tail.score[e] = tail.accumulate ? r0 + sc : sc;
+    }
 }
 
 template <int NEB>
 int launch_mfma(const smoe_layer* L, const void* x, int T, int32_t* oe, float* og, int32_t* sl, float* g,
-                float* xn, int32_t* hist32, hipStream_t s) {
+                float* xn, int32_t* hist32, const TailArgs& tail, hipStream_t s) {
     constexpr int EP = NEB * 32;
     constexpr int NWR = NEB <= 2 ? 8 : 4;
     size_t lds = (size_t)(NWR * EP * RTP + 2 * NWR * RT) * 4;
@@ -406,7 +495,7 @@ int launch_mfma(const smoe_layer* L, const void* x, int T, int32_t* oe, float* o
     }
     hipLaunchKernelGGL(kern, dim3((T + RT - 1) / RT), dim3(NWR * 64), lds, s, (const uint16_t*)x,
                        (const uint4*)L->d_router_split, L->d_expert_to_slot, T, L->cfg.d_model, L->cfg.E,
-                       L->cfg.gate_mode, oe, og, sl, g, xn, hist32, L->cfg.K);
+                       L->cfg.gate_mode, oe, og, sl, g, xn, hist32, L->cfg.K, tail);
     return smoe_check_hip(hipGetLastError(), "smoe_route launch");
 }
 
@@ -460,20 +549,41 @@ int smoe_launch_split_router(const smoe_layer* L, hipStream_t s) {
     return smoe_check_hip(hipGetLastError(), "smoe_route: router split launch");
 }
 
+namespace {
+
+int route_bf16(const smoe_layer* L, const void* x, int T, int32_t* orig_expert, float* orig_gate,
+               int32_t* slot, float* gate, float* xnorm, int32_t* hist32, const TailArgs& tail, hipStream_t s) {
+    switch ((L->cfg.E + 31) / 32) {
+        case 1: return launch_mfma<1>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, tail, s);
+        case 2: return launch_mfma<2>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, tail, s);
+        case 3: return launch_mfma<3>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, tail, s);
+        case 4: return launch_mfma<4>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, tail, s);
+        case 5: return launch_mfma<5>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, tail, s);
+        case 6: return launch_mfma<6>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, tail, s);
+        case 7: return launch_mfma<7>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, tail, s);
+        case 8: return launch_mfma<8>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, tail, s);
+        default: return smoe_fail(SMOE_EINVAL, "smoe_route: E=%d exceeds 256", L->cfg.E);
+    }
+}
+
+}  // namespace
+
 int smoe_launch_route(const smoe_layer* L, const void* x, int T, int32_t* orig_expert,
                       float* orig_gate, int32_t* slot, float* gate, float* xnorm, int32_t* hist32,
                       hipStream_t s) {
     if (L->cfg.dtype == SMOE_F32)
         return dispatch<float>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, s);
-    switch ((L->cfg.E + 31) / 32) {
-        case 1: return launch_mfma<1>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, s);
-        case 2: return launch_mfma<2>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, s);
-        case 3: return launch_mfma<3>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, s);
-        case 4: return launch_mfma<4>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, s);
-        case 5: return launch_mfma<5>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, s);
-        case 6: return launch_mfma<6>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, s);
-        case 7: return launch_mfma<7>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, s);
-        case 8: return launch_mfma<8>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, s);
-        default: return smoe_fail(SMOE_EINVAL, "smoe_route: E=%d exceeds 256", L->cfg.E);
-    }
+    return route_bf16(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, TailArgs{}, s);
+}
+
+// bf16 layers, 1 <= T <= 32: the router's single workgroup also ranks the tokens by slot
+// and adds the importance sums, so the step needs no second launch.
+int smoe_launch_route_rank_small(const smoe_layer* L, const void* x, int T, int32_t* orig_expert,
+                                 float* orig_gate, int32_t* slot, float* gate, float* xnorm, int32_t* count,
+                                 float* gsum, float* score, int accumulate, int32_t* perm, int32_t* inv_perm,
+                                 int32_t* offsets, hipStream_t s) {
+    if (L->cfg.dtype != SMOE_BF16 || T < 1 || T > RT)
+        return smoe_fail(SMOE_EINVAL, "smoe_forward: the one-launch router needs bf16 and 1..%d tokens", RT);
+    const TailArgs tail{L->expert_norm, count, gsum, score, accumulate, perm, inv_perm, offsets};
+    return route_bf16(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, nullptr, tail, s);
 }

@@ -75,6 +75,10 @@ inline int smoe_sort_blocks(int T) { return (T + SMOE_SORT_BLOCK - 1) / SMOE_SOR
 int smoe_launch_route(const smoe_layer* L, const void* x, int T, int32_t* orig_expert,
                       float* orig_gate, int32_t* slot, float* gate, float* xnorm, int32_t* hist32,
                       hipStream_t s);
+int smoe_launch_route_rank_small(const smoe_layer* L, const void* x, int T, int32_t* orig_expert,
+                                 float* orig_gate, int32_t* slot, float* gate, float* xnorm, int32_t* count,
+                                 float* gsum, float* score, int accumulate, int32_t* perm, int32_t* inv_perm,
+                                 int32_t* offsets, hipStream_t s);
 int smoe_launch_rank_importance(const smoe_layer* L, const int32_t* orig_expert, const float* orig_gate,
                                 const float* xnorm, const int32_t* slot, int T, int32_t* count, float* gsum,
                                 float* score, int accumulate, int32_t* perm, int32_t* inv_perm,
@@ -94,7 +98,8 @@ int smoe_launch_ffn_bf16(const smoe_layer* L, const uint16_t* x_perm, const int3
 int smoe_launch_combine(const smoe_layer* L, const void* y_perm, const int32_t* inv_perm,
                         const float* gate, const void* residual, int T, void* out, hipStream_t s);
 // packs / copies one expert's two matrices into physical slot `phys`
-int smoe_launch_pack_slot(const smoe_layer* L, int phys, const void* w1_src, const void* w2_src, hipStream_t s);
+int smoe_launch_pack_slot(const smoe_layer* L, int slot, const void* w1_src, const void* w2_src, hipStream_t s,
+                          int map_slot = -1, int expert = -1, int old_expert = -1, int* map_done = nullptr);
 // slot now serves `expert` from physical slot `phys` (old_expert, if any, leaves the maps)
 int smoe_launch_set_map(const smoe_layer* L, int slot, int expert, int old_expert, int phys, hipStream_t s);
 int smoe_launch_expert_norm(const smoe_layer* L, const void* w1, const void* w2, int n, float* out,
