@@ -359,7 +359,7 @@ def main():
 
     config = {"workload": cfg.name, "E": cfg.E, "K": cfg.K, "d_model": cfg.d_model, "d_ff": cfg.d_ff,
               "tokens": T, "layers": L,
-              "entry": "five separate calls" if args.separate_calls else "smoe_forward (fused, 4 launches)",
+              "entry": "five separate calls" if args.separate_calls else "smoe_forward (fused, 4 launches; 3 when tokens <= 32)",
               "step": "route+importance+permute+expert_ffn+combine over all layers"}
     if decode:
         config.update(update_period=cfg.period, experts_swapped=swaps, updates=args.updates, bank=args.bank,
