@@ -330,7 +330,16 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
     __shared__ int32_t s_oe[RT];
     __shared__ float s_og[RT], s_xn[RT];
     const int st = lane & 31, half = lane >> 5;
+    // Everything below is written with selects, not branches: a compare-and-update under a
+    // lane mask costs the wave a jump per candidate.  Experts past E carry -inf, which never
+    // wins and adds exp(-inf) = 0 to the sums.
+    auto better = [](float ov, int oi, float& bv, int& bidx) {   // the lowest index wins a tie
+        const bool take = (ov > bv) | ((ov == bv) & (oi < bidx));   // no short circuit: no jumps
+        bv = take ? ov : bv;
+        bidx = take ? oi : bidx;
+    };
     float v[EPL];
+    bool res[EPL];
     float best = -INFINITY, rbest = -INFINITY;
     int bi = 0x7fffffff, rbi = 0x7fffffff;
 #pragma unroll
@@ -339,37 +348,35 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
         float sum = part[e * RTP + st];
 #pragma unroll
         for (int w = 1; w < NWR; ++w) sum += part[(w * EP + e) * RTP + st];   // fixed order
-        v[i] = sum;
-        if (e < E) {                              // ascending e: the lowest index wins a tie
-            if (sum > best) { best = sum; bi = e; }
-            if (s_e2s[e] >= 0 && sum > rbest) { rbest = sum; rbi = e; }
-        }
+        res[i] = s_e2s[e] >= 0;                   // -1 past E as well
+        v[i] = e < E ? sum : -INFINITY;
+        better(v[i], e, best, bi);                // ascending e within the lane
+        better(res[i] ? v[i] : -INFINITY, res[i] ? e : 0x7fffffff, rbest, rbi);
     }
-    {
-        float ov = __shfl_xor(best, 32); int oi = __shfl_xor(bi, 32);
-        if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
-        float rv = __shfl_xor(rbest, 32); int ri = __shfl_xor(rbi, 32);
-        if (rv > rbest || (rv == rbest && ri < rbi)) { rbest = rv; rbi = ri; }
-    }
+    better(__shfl_xor(best, 32), __shfl_xor(bi, 32), best, bi);
+    better(__shfl_xor(rbest, 32), __shfl_xor(rbi, 32), rbest, rbi);
     if (half == 0) { s_best[wave][st] = best; s_bi[wave][st] = bi; s_rbest[wave][st] = rbest; s_rbi[wave][st] = rbi; }
     __syncthreads();
-    best = s_best[0][st]; bi = s_bi[0][st]; rbest = s_rbest[0][st]; rbi = s_rbi[0][st];
+    {
+        float wb[NWR], wrb[NWR];
+        int wi[NWR], wri[NWR];
 #pragma unroll
-    for (int w = 1; w < NWR; ++w) {
-        const float ov = s_best[w][st]; const int oi = s_bi[w][st];
-        if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
-        const float rv = s_rbest[w][st]; const int ri = s_rbi[w][st];
-        if (rv > rbest || (rv == rbest && ri < rbi)) { rbest = rv; rbi = ri; }
+        for (int w = 0; w < NWR; ++w) {           // all the reads first, then the merges in wave order
+            wb[w] = s_best[w][st]; wi[w] = s_bi[w][st]; wrb[w] = s_rbest[w][st]; wri[w] = s_rbi[w][st];
+        }
+        best = wb[0]; bi = wi[0]; rbest = wrb[0]; rbi = wri[0];
+#pragma unroll
+        for (int w = 1; w < NWR; ++w) {
+            better(wb[w], wi[w], best, bi);
+            better(wrb[w], wri[w], rbest, rbi);
+        }
     }
     float z = 0.f, zr = 0.f;
 #pragma unroll
     for (int i = 0; i < EPL; ++i) {
-        const int e = wave * 2 + half + EG * i;
-        if (e < E) {
-            const float p = expf(v[i] - best);
-            z += p;
-            if (s_e2s[e] >= 0) zr += p;
-        }
+        const float p = expf(v[i] - best);
+        z += p;
+        zr += res[i] ? p : 0.f;
     }
     z += __shfl_xor(z, 32);
     zr += __shfl_xor(zr, 32);
@@ -458,7 +465,7 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
         float g[RT], r[RT];
 #pragma unroll
         for (int t = 0; t < RT; ++t) {                         // same address in every lane: LDS broadcasts
-            const bool hit = t < T && s_oe[t] == e;
+            const bool hit = (t < T) & (s_oe[t] == e);
             c += hit;
             g[t] = hit ? s_og[t] : 0.f;
             r[t] = hit ? s_xn[t] * s_og[t] : 0.f;
