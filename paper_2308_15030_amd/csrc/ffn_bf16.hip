@@ -171,11 +171,11 @@ __device__ __forceinline__ void apply_gate(float& v0, float& v1, float& v2, floa
 //   BKT   reduction slice per LDS stage    PD    weight prefetch distance in slices
 //   XFRAG token operand X is in fragment order (else row-major [T, R])
 //   YFRAG output Y is written in fragment order (else row-major [T, N])
-template <int AF, int NBF, int NW, int BKT, int PD, bool XFRAG, bool YFRAG, bool RELU>
+template <int AF, int NBF, int NW, int BKT, int PD, bool XFRAG, bool YFRAG, bool RELU, bool EARLY>
 __device__ __forceinline__ void run_tile(const uint16_t* __restrict__ X, const uint4* __restrict__ Wp,
                                          uint16_t* __restrict__ Y, int R, int N, int slot, int m0,
                                          int m_end, int pm0, int ftile, uint16_t* xs, int stage_elems,
-                                         const FuseArgs fz) {
+                                         int* orow, float* ogate, const FuseArgs fz) {
     constexpr int THREADS = NW * 64;
     constexpr int KS = BKT / 16;
     constexpr int LDR = BKT + KPAD;
@@ -217,6 +217,22 @@ __device__ __forceinline__ void run_tile(const uint16_t* __restrict__ X, const u
     const int xoff = XFRAG ? ((lane >> 5) * 32 + (lane & 31)) * 8 : (lane & 31) * LDR + (lane >> 5) * 8;
     constexpr int XB = XFRAG ? CPR * 32 * 8 : 32 * LDR;   // token block stride in LDS
     constexpr int XK = XFRAG ? 2 * 32 * 8 : 16;           // reduction step stride in LDS
+
+    // Row-major output: where each row of the tile goes (out[perm[row]] in the single-call
+    // path, y_perm[row] otherwise; -1 past the segment's end) and its gate are fetched now,
+    // a whole reduction before the epilogue needs them.
+    if (!YFRAG) {
+        for (int r = tid; r < 32 * NBF; r += THREADS) {
+            int dst = -1;
+            float g = 1.f;
+            if (m0 + r < m_end) {
+                dst = fz.perm ? fz.perm[m0 + r] : m0 + r;
+                if (fz.perm) g = fz.gate[dst];
+            }
+            orow[r] = dst;
+            ogate[r] = g;
+        }
+    }
 
     f32x16 acc[AF][NBF];
 #pragma unroll
@@ -273,6 +289,23 @@ __device__ __forceinline__ void run_tile(const uint16_t* __restrict__ X, const u
         for (int i = 0; i < CPT; ++i) tregA[i] = *(const uint4*)(tsrc[i] + (size_t)c2 * tstep);
     }
     __syncthreads();
+    // Row-major output, single-call path: the residual rows come from far away by now (two
+    // weight streams have passed through the caches since x was read), so small tiles ask for
+    // their pieces here and carry them through the reduction in registers.
+    constexpr int OF = NW * AF * 32;                      // features of the workgroup tile
+    constexpr int OCPR = OF / 8;                          // 16-byte pieces per output row
+    constexpr int ONP = YFRAG ? 1 : 32 * NBF * OCPR / THREADS;   // pieces per thread (2 * NBF * AF)
+    constexpr bool EARLY_RES = !YFRAG && EARLY;           // the launcher knows the register budget
+    uint4 res[EARLY_RES ? ONP : 1];
+    if (EARLY_RES && fz.perm && fz.residual) {
+#pragma unroll
+        for (int i = 0; i < ONP; ++i) {
+            const int idx = tid + i * THREADS, r = idx / OCPR, c = idx % OCPR;
+            const int col = ftile * OF + c * 8, row = col < N ? orow[r] : -1;
+            res[i] = make_uint4(0, 0, 0, 0);
+            if (row >= 0) res[i] = *(const uint4*)(fz.residual + (size_t)row * N + col);
+        }
+    }
 #pragma unroll
     for (int b = 0; b < GB; ++b) xf[0][b] = as_frag(*(const uint4*)&xs[xoff + b * XB]);
 
@@ -339,54 +372,112 @@ __device__ __forceinline__ void run_tile(const uint16_t* __restrict__ X, const u
     __syncthreads();                                      // the next tile's first write may hit any stage
 
     // accumulator register i of lane l: feature 8*(i/4) + 4*(l/32) + i%4, token l%32
+    if constexpr (YFRAG) {   // unit [(pm0/32 + b)][(fb0+a)*4 + g][lane%32], 8 bytes at half (lane/32)
 #pragma unroll
-    for (int a = 0; a < AF; ++a) {
-        if (fb0 + a >= nfb) continue;
+        for (int a = 0; a < AF; ++a) {
+            if (fb0 + a >= nfb) continue;
 #pragma unroll
-        for (int b = 0; b < NBF; ++b) {
-            uint16_t* ydst;
-            const uint16_t* rsrc = nullptr;
-            float gmul = 1.f;
-            if (YFRAG) {   // unit [(pm0/32 + b)][(fb0+a)*4 + g][lane%32], 8 bytes at half (lane/32)
-                ydst = Y + (((size_t)((pm0 >> 5) + b) * (N >> 3) + (fb0 + a) * 4) * 32 + (lane & 31)) * 8 +
-                       (lane >> 5) * 4;
-            } else {
-                int row = m0 + b * 32 + (lane & 31);
-                if (row >= m_end) continue;
-                if (fz.perm) {
-                    row = fz.perm[row];
-                    gmul = fz.gate[row];
-                    if (fz.residual) rsrc = fz.residual + (size_t)row * N + (fb0 + a) * 32 + (lane >> 5) * 4;
+            for (int b = 0; b < NBF; ++b) {
+                uint16_t* ydst = Y + (((size_t)((pm0 >> 5) + b) * (N >> 3) + (fb0 + a) * 4) * 32 + (lane & 31)) * 8 +
+                                 (lane >> 5) * 4;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    float v0 = acc[a][b][4 * g], v1 = acc[a][b][4 * g + 1], v2 = acc[a][b][4 * g + 2],
+                          v3 = acc[a][b][4 * g + 3];
+                    if (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
+                    uint2 o;
+                    o.x = (uint32_t)smoe_f32_to_bf16(v0) | ((uint32_t)smoe_f32_to_bf16(v1) << 16);
+                    o.y = (uint32_t)smoe_f32_to_bf16(v2) | ((uint32_t)smoe_f32_to_bf16(v3) << 16);
+                    *(uint2*)(ydst + g * 32 * 8) = o;
                 }
-                ydst = Y + (size_t)row * N + (fb0 + a) * 32 + (lane >> 5) * 4;
-            }
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                float v0 = acc[a][b][4 * g], v1 = acc[a][b][4 * g + 1], v2 = acc[a][b][4 * g + 2],
-                      v3 = acc[a][b][4 * g + 3];
-                if (!YFRAG) apply_gate(v0, v1, v2, v3, gmul, rsrc ? rsrc + g * 8 : nullptr, fz.perm != nullptr);
-                if (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
-                uint2 o;
-                o.x = (uint32_t)smoe_f32_to_bf16(v0) | ((uint32_t)smoe_f32_to_bf16(v1) << 16);
-                o.y = (uint32_t)smoe_f32_to_bf16(v2) | ((uint32_t)smoe_f32_to_bf16(v3) << 16);
-                *(uint2*)(ydst + (YFRAG ? g * 32 * 8 : g * 8)) = o;
             }
         }
+    } else {
+        // Row-major output.  In the accumulator layout a store instruction would touch 32 rows
+        // with 8 bytes each; the tile is turned through LDS instead (the ring is idle now), so
+        // that 16 lanes write one row's 256 contiguous bytes.  The product is rounded to bf16
+        // on the way in -- the value the plain path stores, and the one the fused path scales
+        // by the gate (+ residual) in fp32 before its single final rounding.
+        constexpr int F = OF, CPR8 = OCPR, NP = ONP;
+        constexpr int LDO = F + 4;                        // LDS row pitch in elements (8-byte aligned rows)
+        static_assert(32 * NBF * CPR8 % THREADS == 0, "pieces divide evenly");
+#pragma unroll
+        for (int a = 0; a < AF; ++a)
+#pragma unroll
+            for (int b = 0; b < NBF; ++b)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    float v0 = acc[a][b][4 * g], v1 = acc[a][b][4 * g + 1], v2 = acc[a][b][4 * g + 2],
+                          v3 = acc[a][b][4 * g + 3];
+                    if (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
+                    uint2 o;
+                    o.x = (uint32_t)smoe_f32_to_bf16(v0) | ((uint32_t)smoe_f32_to_bf16(v1) << 16);
+                    o.y = (uint32_t)smoe_f32_to_bf16(v2) | ((uint32_t)smoe_f32_to_bf16(v3) << 16);
+                    *(uint2*)&xs[(b * 32 + (lane & 31)) * LDO + (wave * AF + a) * 32 + g * 8 + (lane >> 5) * 4] = o;
+                }
+        __syncthreads();
+        const bool fused = fz.perm != nullptr, has_res = fused && fz.residual != nullptr;
+        const int col0 = ftile * F;
+        constexpr int CH = NP < 8 ? NP : 8;               // pieces handled together (bounds the registers)
+#pragma unroll
+        for (int i0 = 0; i0 < NP; i0 += CH) {
+            int prow[CH], pcol[CH];
+            uint4 rs[CH];
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {                // residual pieces not fetched earlier are asked for first
+                const int idx = tid + (i0 + j) * THREADS, r = idx / CPR8, c = idx % CPR8;
+                pcol[j] = col0 + c * 8;
+                prow[j] = pcol[j] < N ? orow[r] : -1;
+                if constexpr (EARLY_RES) {
+                    rs[j] = res[i0 + j];
+                } else {
+                    rs[j] = make_uint4(0, 0, 0, 0);
+                    if (has_res && prow[j] >= 0) rs[j] = *(const uint4*)(fz.residual + (size_t)prow[j] * N + pcol[j]);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+                if (prow[j] < 0) continue;
+                const int idx = tid + (i0 + j) * THREADS, r = idx / CPR8, c = idx % CPR8;
+                const uint2 lo = *(const uint2*)&xs[r * LDO + c * 8], hi = *(const uint2*)&xs[r * LDO + c * 8 + 4];
+                uint4 o = make_uint4(lo.x, lo.y, hi.x, hi.y);
+                if (fused) {
+                    const float g = ogate[r];
+                    uint32_t yw[4] = {o.x, o.y, o.z, o.w}, rw[4] = {rs[j].x, rs[j].y, rs[j].z, rs[j].w};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float y0 = __uint_as_float(yw[q] << 16), y1 = __uint_as_float(yw[q] & 0xFFFF0000u);
+                        float o0, o1;
+                        if (has_res) {
+                            o0 = fmaf(g, y0, __uint_as_float(rw[q] << 16));
+                            o1 = fmaf(g, y1, __uint_as_float(rw[q] & 0xFFFF0000u));
+                        } else {
+                            o0 = g * y0;
+                            o1 = g * y1;
+                        }
+                        yw[q] = (uint32_t)smoe_f32_to_bf16(o0) | ((uint32_t)smoe_f32_to_bf16(o1) << 16);
+                    }
+                    o = make_uint4(yw[0], yw[1], yw[2], yw[3]);
+                }
+                *(uint4*)(Y + (size_t)prow[j] * N + pcol[j]) = o;
+            }
+        }
+        __syncthreads();                                  // the next tile's prologue reuses the ring
     }
 }
 
-template <int AF, int NBF, int MAXB, int NW, int BKT, int PD, bool XFRAG, bool YFRAG, bool RELU>
+template <int AF, int NBF, int MAXB, int NW, int BKT, int PD, bool XFRAG, bool YFRAG, bool RELU, bool EARLY>
 struct TileSwitch {
     static __device__ __forceinline__ void go(int nbf, const uint16_t* X, const uint4* Wp, uint16_t* Y, int R,
                                               int N, int slot, int m0, int m_end, int pm0, int ftile,
-                                              uint16_t* xs, const FuseArgs fz) {
+                                              uint16_t* xs, int* orow, float* ogate, const FuseArgs fz) {
         constexpr int stage = MAXB * 32 * (BKT + KPAD);
         if (nbf == NBF)
-            run_tile<AF, NBF, NW, BKT, PD, XFRAG, YFRAG, RELU>(X, Wp, Y, R, N, slot, m0, m_end, pm0, ftile, xs,
-                                                               stage, fz);
+            run_tile<AF, NBF, NW, BKT, PD, XFRAG, YFRAG, RELU, EARLY>(X, Wp, Y, R, N, slot, m0, m_end, pm0, ftile, xs,
+                                                               stage, orow, ogate, fz);
         else if constexpr (NBF > 1)
-            TileSwitch<AF, NBF - 1, MAXB, NW, BKT, PD, XFRAG, YFRAG, RELU>::go(nbf, X, Wp, Y, R, N, slot, m0,
-                                                                              m_end, pm0, ftile, xs, fz);
+            TileSwitch<AF, NBF - 1, MAXB, NW, BKT, PD, XFRAG, YFRAG, RELU, EARLY>::go(nbf, X, Wp, Y, R, N, slot, m0,
+                                                                              m_end, pm0, ftile, xs, orow, ogate, fz);
     }
 };
 
@@ -397,7 +488,11 @@ template <int AF, int MAXB, int NW, int BKT, int PD, int OCC, bool FIRST>
 __global__ __launch_bounds__(NW * 64, OCC) void grouped_gemm_bf16(
     const uint16_t* __restrict__ X, const uint4* __restrict__ Wp, const int32_t* __restrict__ offsets,
     int nslots, int T, uint16_t* __restrict__ Y, int R, int N, const FuseArgs fz) {
-    __shared__ __align__(16) uint16_t xs[3 * MAXB * 32 * (BKT + KPAD)];
+    // the ring of token stages; the second product's epilogue turns its output tile through it
+    constexpr int RING = 3 * MAXB * 32 * (BKT + KPAD), OUT_TILE = FIRST ? 0 : MAXB * 32 * (NW * AF * 32 + 4);
+    __shared__ __align__(16) uint16_t xs[RING > OUT_TILE ? RING : OUT_TILE];
+    __shared__ int s_orow[MAXB * 32];
+    __shared__ float s_ogate[MAXB * 32];
     __shared__ ItemMap map;
     constexpr int BT = MAXB * 32;
     const int ftiles = ((N >> 5) + NW * AF - 1) / (NW * AF);
@@ -413,8 +508,8 @@ __global__ __launch_bounds__(NW * 64, OCC) void grouped_gemm_bf16(
         row_tile_at(map, nslots, BT, mt, slot, m0, m_end, pm0);
         if (fz.phys) slot = __builtin_amdgcn_readfirstlane(fz.phys[slot]);   // from here on: where the weights live
         const int nbf = min(MAXB, (m_end - m0 + 31) >> 5);    // token blocks that hold real rows
-        TileSwitch<AF, MAXB, MAXB, NW, BKT, PD, !FIRST, FIRST, FIRST>::go(nbf, X, Wp, Y, R, N, slot, m0, m_end,
-                                                                         pm0, ftile, xs, fz);
+        TileSwitch<AF, MAXB, MAXB, NW, BKT, PD, !FIRST, FIRST, FIRST, !FIRST && AF * MAXB <= 4 && OCC <= 2>::go(nbf, X, Wp, Y, R, N, slot, m0, m_end,
+                                                                         pm0, ftile, xs, s_orow, s_ogate, fz);
     }
 }
 
