@@ -47,7 +47,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per grouped-GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on
 # the default command (profiles/grouped_gemm_bf16_c3_prefill_hbm_counters.txt), mean of the two
 # launches of one FFN; None for any other configuration.
-MEASURED_TRAFFIC_C3 = 143.8e6
+MEASURED_TRAFFIC_C3 = 144.6e6
 
 
 def dev_t(a, dev):
