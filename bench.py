@@ -48,6 +48,8 @@ PEAK_HBM_GBS = 8000.0
 # the default command (profiles/grouped_gemm_bf16_c3_prefill_hbm_counters.txt), mean of the two
 # launches of one FFN; None for any other configuration.
 MEASURED_TRAFFIC_C3 = 144.6e6
+# the same for the decode products (profiles/dense_gemm_bf16_c4_decode_hbm_counters.txt), default c4 run
+MEASURED_TRAFFIC_C4 = 67.0e6
 
 
 def dev_t(a, dev):
@@ -324,11 +326,14 @@ def main():
                     "hbm_frac": round(bytes_launch / avg / 1e9 / PEAK_HBM_GBS, 4)}
         else:
             act = float(np.mean(active_log)) if active_log else float(cfg.K)
+            default_c4 = (args.workload == "c4" and args.updates == "sync" and args.bank == "device"
+                          and args.policy == "importance" and args.period is None and not args.separate_calls
+                          and args.decode_layers == 1)
             bytes_launch = 2.0 * act * cfg.d_model * cfg.d_ff  # one weight matrix of every active slot
             achieved = bytes_launch / avg / 1e9
             roof = {"bound": "hbm", "kernel": "dense_gemm_bf16 / small_gemm_bf16 (mean of the FFN's two launches)",
                     "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None,
+                    "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": MEASURED_TRAFFIC_C4 if default_c4 else None,
                     "us_per_launch": round(avg * 1e6, 2), "us_gemm1": round(g1.mean() * 1e6, 2),
                     "us_gemm2": round(g2.mean() * 1e6, 2), "launches_timed": 2 * len(ev_used),
                     "mean_active_slots": round(act, 2),
