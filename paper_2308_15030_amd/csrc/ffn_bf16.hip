@@ -296,6 +296,18 @@ __device__ __forceinline__ void run_tile(const uint16_t* __restrict__ X, const u
     constexpr int OCPR = OF / 8;                          // 16-byte pieces per output row
     constexpr int ONP = YFRAG ? 1 : 32 * NBF * OCPR / THREADS;   // pieces per thread (2 * NBF * AF)
     constexpr bool EARLY_RES = !YFRAG && EARLY;           // the launcher knows the register budget
+    // small tiles store straight from the accumulator layout: this lane's rows and gates, taken
+    // from the tables now (the next tile refills the tables while slower waves are still storing)
+    constexpr int NDIRECT = (!YFRAG && NBF <= 2 && !EARLY) ? NBF : 1;
+    int drow[NDIRECT];
+    float dgate[NDIRECT];
+    if constexpr (!YFRAG && NBF <= 2 && !EARLY) {
+#pragma unroll
+        for (int b = 0; b < NBF; ++b) {
+            drow[b] = orow[b * 32 + (lane & 31)];
+            dgate[b] = ogate[b * 32 + (lane & 31)];
+        }
+    }
     uint4 res[EARLY_RES ? ONP : 1];
     if (EARLY_RES && fz.perm && fz.residual) {
 #pragma unroll
@@ -389,6 +401,44 @@ __device__ __forceinline__ void run_tile(const uint16_t* __restrict__ X, const u
                     o.x = (uint32_t)smoe_f32_to_bf16(v0) | ((uint32_t)smoe_f32_to_bf16(v1) << 16);
                     o.y = (uint32_t)smoe_f32_to_bf16(v2) | ((uint32_t)smoe_f32_to_bf16(v3) << 16);
                     *(uint2*)(ydst + g * 32 * 8) = o;
+                }
+            }
+        }
+    } else if constexpr (NBF <= 2 && !EARLY) {
+        // Row-major output of a small tile of the small-tile kernels, straight from the accumulator layout (a lane holds 4
+        // consecutive features of one token): the two extra barriers of the LDS turn below cost
+        // more than the scattered 8-byte stores of at most two token blocks.
+        const bool fused = fz.perm != nullptr, has_res = fused && fz.residual != nullptr;
+#pragma unroll
+        for (int a = 0; a < AF; ++a) {
+            if (fb0 + a >= nfb) continue;
+            const int col = (fb0 + a) * 32 + (lane >> 5) * 4;
+            int dst[NBF];
+            uint2 rr[NBF][4];
+#pragma unroll
+            for (int b = 0; b < NBF; ++b) {       // every residual piece of this feature block is asked for first
+                dst[b] = drow[b];
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    rr[b][g] = make_uint2(0, 0);
+                    if (has_res && dst[b] >= 0) rr[b][g] = *(const uint2*)(fz.residual + (size_t)dst[b] * N + col + g * 8);
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < NBF; ++b) {
+                if (dst[b] < 0) continue;
+                const float gmul = dgate[b];
+                uint16_t* ydst = Y + (size_t)dst[b] * N + col;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    float v0 = acc[a][b][4 * g], v1 = acc[a][b][4 * g + 1], v2 = acc[a][b][4 * g + 2],
+                          v3 = acc[a][b][4 * g + 3];
+                    apply_gate_v(v0, v1, v2, v3, gmul, rr[b][g], has_res, fused);
+                    if (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
+                    uint2 o;
+                    o.x = (uint32_t)smoe_f32_to_bf16(v0) | ((uint32_t)smoe_f32_to_bf16(v1) << 16);
+                    o.y = (uint32_t)smoe_f32_to_bf16(v2) | ((uint32_t)smoe_f32_to_bf16(v3) << 16);
+                    *(uint2*)(ydst + g * 8) = o;
                 }
             }
         }
