@@ -915,11 +915,16 @@ void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* off
 // Tile shapes for the two GEMMs.  SMOE_FFN_VARIANT="v1,v2" overrides the
 // built-in choice (a tuning aid; the indices are those of launch_variant).
 void pick_variants(const smoe_config& c, int T, int& v1, int& v2) {
+    // Thresholds measured on the Switch-base-64 shape (K = 16, 768 x 3072) over T = 48 .. 8192.
+    // What decides in the middle range is whether the first product's tiles fit the chip in one
+    // round (256-row tiles at 120-183 tokens per slot: one tile per slot and feature tile).
     int per_slot = T / c.K;
     if (per_slot >= 384) { v1 = 10; v2 = 1; }
-    else if (per_slot >= 96) { v1 = 8; v2 = 1; }
-    else if (per_slot >= 48) { v1 = 2; v2 = 3; }
-    else if (per_slot >= 8) { v1 = 4; v2 = 4; }
+    else if (per_slot >= 184) { v1 = 8; v2 = 1; }
+    else if (per_slot >= 120) { v1 = 10; v2 = 3; }
+    else if (per_slot >= 60) { v1 = 8; v2 = 3; }
+    else if (per_slot >= 28) { v1 = 3; v2 = 4; }
+    else if (per_slot >= 6) { v1 = 4; v2 = 6; }
     else { v1 = 5; v2 = 6; }             // decode: a few tokens per slot, weight streaming
     const char* env = getenv("SMOE_FFN_VARIANT");
     if (env) {
