@@ -81,6 +81,51 @@ def make_layer(b, wl, cfg, l, experts, dev, spare_slots=0, pinned_bank=False):
     return lay, (d1, d2), (Wr, W1, W2)
 
 
+def per_call(args, cfg, layers, wl, dev, T, L):
+    """Median duration of every hot call on its own (events on the caller's stream around one call,
+    cycling through the layers so weights come from HBM as in the throughput run), with the
+    algorithmic bytes / flops of the step and the fractions of the published peaks."""
+    import numpy as np
+    import torch
+    xs = [dev_t(wl.hidden_states(cfg, l) if cfg.period == 0 else wl.decode_stream(cfg, 1)[0], dev) for l in range(L)]
+    d, f, E, K = cfg.d_model, cfg.d_ff, cfg.E, cfg.K
+    for lay, x in zip(layers, xs):                       # every buffer holds a consistent state
+        lay.forward(x, T, accumulate=0, residual=x)
+    torch.cuda.synchronize()
+    act = float(np.mean([(lay.offsets[1:] > lay.offsets[:-1]).sum().item() for lay in layers]))
+    calls = {   # name: (callable(layer, x), algorithmic bytes, flops)
+        "smoe_route": (lambda lay, x: lay.route(x, T), T * d * 2 + 20 * T + E * d * 4, 2.0 * T * d * E),
+        "smoe_importance": (lambda lay, x: lay.importance(T, 1), 12 * T + 12 * E, 0.0),
+        "smoe_permute": (lambda lay, x: lay.permute(x, T), 2 * T * d * 2 + 12 * T, 0.0),
+        "smoe_expert_ffn": (lambda lay, x: lay.expert_ffn(T), act * 2 * d * f * 2 + 2 * T * d * 2, 4.0 * T * d * f),
+        "smoe_combine": (lambda lay, x: lay.combine(T, residual=x), 3 * T * d * 2 + 8 * T, 0.0),
+        "smoe_forward": (lambda lay, x: lay.forward_fused(x, T, accumulate=1, residual=x),
+                         act * 2 * d * f * 2 + 3 * T * d * 2 + 20 * T, 4.0 * T * d * f + 2.0 * T * d * E),
+    }
+    one = torch.zeros(1, device=dev)
+    calls["(floor: event pair around nothing)"] = (lambda lay, x: None, 0, 0.0)
+    calls["(floor: event pair around a one-element fill kernel)"] = (lambda lay, x: one.zero_(), 0, 0.0)
+    out = {}
+    n_warm, n_iter = 10, 100
+    for name, (fn, nbytes, flops) in calls.items():
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_iter)]
+        for i in range(n_warm + n_iter):
+            lay, x = layers[i % L], xs[i % L]
+            if i >= n_warm:
+                evs[i - n_warm][0].record()
+            fn(lay, x)
+            if i >= n_warm:
+                evs[i - n_warm][1].record()
+        torch.cuda.synchronize()
+        us = float(np.median([a.elapsed_time(b) for a, b in evs])) * 1e3
+        out[name] = {"us": round(us, 2), "bytes": int(nbytes), "GBs": round(nbytes / us / 1e3, 1),
+                     "hbm_frac": round(nbytes / us / 1e3 / PEAK_HBM_GBS, 4),
+                     "TFLOPs": round(flops / us / 1e6, 1), "mfma_frac": round(flops / us / 1e6 / PEAK_BF16_MFMA_TFLOPS, 4)}
+    print(json.dumps({"per_call": out, "workload": cfg.name, "tokens": T, "layers_cycled": L,
+                      "mean_active_slots": round(act, 2), "iterations": n_iter, "warmup": n_warm,
+                      "note": "median of per-call event pairs; bytes = algorithmic (inputs, outputs and active slots' weights once)"}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -112,6 +157,9 @@ def main():
                     help="c4 only: decode steps the host may enqueue ahead of the GPU (a serving loop reads each "
                          "step's tokens before it can issue the next; unbounded run-ahead would also make "
                          "'between two steps' meaningless for the asynchronous updates)")
+    ap.add_argument("--per-call", action="store_true",
+                    help="instead of the throughput run: median time of each of the five hot calls (and of "
+                         "smoe_forward) over 100 iterations after 10 warm-ups, with the bytes and flops each moves")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--separate-calls", action="store_true",
                     help="drive the layer through the five per-step calls instead of smoe_forward")
@@ -155,6 +203,10 @@ def main():
 
     def fwd(lay):
         return lay.forward if args.separate_calls else lay.forward_fused
+
+    if args.per_call:
+        per_call(args, cfg, layers, wl, dev, T, L)
+        return
 
     # Per-kernel events ride on the two grouped-GEMM dispatches of ONE layer call per
     # sampled step (layer k % L at step k; decode samples every 4th step): each pair
