@@ -28,7 +28,9 @@ pinned` keeps the bank in host memory, so loads cross PCIe.
 
 Prints ONE JSON line.  `roofline` is for the expert FFN's two grouped-GEMM
 launches: their duration is measured live with HIP events attached to the two
-product dispatches of one layer call per sampled step of the timed region.
+product dispatches of one layer call per sampled step, in a second pass over
+the same K steps right after the throughput pass (a dispatch that carries
+events stalls the queue behind it, so the two cannot share a pass).
 `cpu_baseline` times the CPU oracle on a bounded sample of the same workload on
 this machine's host cores.
 """
@@ -153,10 +155,12 @@ def main():
     ap.add_argument("--bank", default="device", choices=["device", "pinned"],
                     help="c4 only: where the full expert bank lives (pinned = host memory read over PCIe)")
     ap.add_argument("--spare-slots", type=int, default=1, help="c4 --updates async: spare physical slots")
-    ap.add_argument("--max-ahead", type=int, default=2,
-                    help="c4 only: decode steps the host may enqueue ahead of the GPU (a serving loop reads each "
-                         "step's tokens before it can issue the next; unbounded run-ahead would also make "
-                         "'between two steps' meaningless for the asynchronous updates)")
+    ap.add_argument("--max-ahead", type=int, default=None,
+                    help="c4 only: decode steps the host may enqueue ahead of the GPU, enforced with one event "
+                         "per step (default: 2 with --updates async, where unbounded run-ahead would make "
+                         "'between two steps' meaningless; otherwise no pacing -- the synchronous update's "
+                         "score read-back already stops the host every period, and an event per step costs "
+                         "the GPU queue about 14 us per step)")
     ap.add_argument("--per-call", action="store_true",
                     help="instead of the throughput run: median time of each of the five hot calls (and of "
                          "smoe_forward) over 100 iterations after 10 warm-ups, with the bytes and flops each moves")
@@ -164,7 +168,7 @@ def main():
     ap.add_argument("--separate-calls", action="store_true",
                     help="drive the layer through the five per-step calls instead of smoe_forward")
     ap.add_argument("--no-events", action="store_true",
-                    help="do not record per-kernel events inside the timed region")
+                    help="skip the second, instrumented pass (no roofline)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
@@ -208,11 +212,13 @@ def main():
         per_call(args, cfg, layers, wl, dev, T, L)
         return
 
-    # Per-kernel events ride on the two grouped-GEMM dispatches of ONE layer call per
-    # sampled step (layer k % L at step k; decode samples every 4th step): each pair
-    # reads the start and end of that kernel's execution.  Timed dispatches carry a
-    # completion signal each, so attaching events to every call would slow the very
-    # region whose throughput is being measured.
+    # Two passes over the same K steps.  The first is the throughput measurement: nothing but the
+    # hot path between the two synchronisations.  The second repeats the K steps with per-kernel
+    # events riding on the two grouped-GEMM dispatches of ONE layer call per sampled step (layer
+    # k % L at step k; decode samples every 4th step); each pair reads the start and end of that
+    # kernel's execution and feeds `roofline`.  A dispatch that carries events also carries a
+    # completion signal and stalls the queue behind it (5 % at c3, 20 % on the decode step), so
+    # the two measurements cannot share a pass.
     ev_stride = 4 if decode else 1
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)] if use_events else []
     ev_used = []
@@ -236,9 +242,13 @@ def main():
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for k in range(steps):
-            step(k)
+            step()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
+        if use_events:
+            for k in range(steps):
+                step(k)
+            torch.cuda.synchronize()
     else:
         xs_host = wl.decode_stream(cfg, warmup + steps)
         xs = dev_t(xs_host.reshape(-1, cfg.d_model), dev).view(warmup + steps, T, cfg.d_model)
@@ -287,10 +297,11 @@ def main():
         score_host = [torch.zeros(cfg.E, dtype=torch.float32).pin_memory() for _ in layers]
         score_ev = [torch.cuda.Event() for _ in layers]
         score_due = [False] * L
-        ahead = max(1, args.max_ahead)
+        ahead = args.max_ahead if args.max_ahead is not None else (2 if args.updates == "async" else 0)
+        ahead = max(0, ahead)
         step_done = [torch.cuda.Event() for _ in range(ahead + 1)]
 
-        def run(first, n, timed):
+        def run(first, n, timed, instrument=False):
             swaps = 0
             for i in range(n):
                 sidx = first + i
@@ -305,7 +316,7 @@ def main():
                     x_in.copy_(x, non_blocking=True)
                     graphs[0 if sidx % cfg.period == 0 else 1].replay()
                 for l, lay in enumerate(layers if not args.graph else []):
-                    sampled = timed and i % ev_stride == 0 and l == (i // ev_stride) % L
+                    sampled = instrument and i % ev_stride == 0 and l == (i // ev_stride) % L
                     if sampled and use_events:
                         b.smoe_set_profile_events(lay.handle, *evs[i])
                         ev_used.append(i)
@@ -327,9 +338,10 @@ def main():
                             lay.set_resident(sl, int(ex), d1[int(ex)], d2[int(ex)])
                             last_use[l][sl] = sidx + 1
                             swaps += 1
-                step_done[i % (ahead + 1)].record()
-                if i >= ahead:
-                    step_done[(i - ahead) % (ahead + 1)].synchronize()
+                if ahead > 0:
+                    step_done[i % (ahead + 1)].record()
+                    if i >= ahead:
+                        step_done[(i - ahead) % (ahead + 1)].synchronize()
                 if (sidx + 1) % cfg.period == 0 and args.updates != "none" and args.policy != "lru":
                     for l, (lay, (d1, d2)) in enumerate(zip(layers, banks)):
                         if args.updates == "async":          # scores travel to the host behind the compute stream
@@ -349,6 +361,8 @@ def main():
         t0 = time.perf_counter()
         swaps = run(warmup, steps, True)
         dt = time.perf_counter() - t0
+        if use_events:          # the same steps again, instrumented (the resident set carries on from the first pass)
+            run(warmup, steps, False, instrument=True)
         active_log = (offs_log[:, 1:] > offs_log[:, :-1]).sum(dim=1).cpu().numpy().tolist()
         hit_rate = None
         if args.hit_rate:
@@ -420,7 +434,7 @@ def main():
               "step": "route+importance+permute+expert_ffn+combine over all layers"}
     if decode:
         config.update(update_period=cfg.period, experts_swapped=swaps, updates=args.updates, bank=args.bank,
-                      host_steps_ahead=max(1, args.max_ahead), policy=args.policy, hip_graph=bool(args.graph),
+                      host_steps_ahead=(ahead if ahead > 0 else "unpaced"), policy=args.policy, hip_graph=bool(args.graph),
                       hit_rate=None if hit_rate is None else round(hit_rate, 4),
                       bytes_loaded_per_step=round(swaps * 2.0 * cfg.d_model * cfg.d_ff * 2 / steps, 1),
                       spare_slots=args.spare_slots if args.updates == "async" else 0,
