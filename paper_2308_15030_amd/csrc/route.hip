@@ -237,8 +237,11 @@ struct TailArgs {
     int32_t* offsets;
 };
 
-// NEB = 32-expert blocks, NWR = waves per workgroup (each takes 1/NWR of d_model).
-template <int NEB, int NWR>
+// NEB = 32-expert blocks, NWR = waves per workgroup (each takes 1/NWR of d_model),
+// TB = 32-token blocks per workgroup: every workgroup streams the whole router once, so
+// when the batch has more 32-token blocks than the chip has compute units a workgroup takes
+// two blocks and the weights are fetched half as often.
+template <int NEB, int NWR, int TB>
 __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
     const uint16_t* __restrict__ x, const uint4* __restrict__ Wsplit, const int32_t* __restrict__ e2s,
     int T, int d, int E, int gate_mode,
@@ -247,42 +250,54 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
     const TailArgs tail) {
     extern __shared__ __align__(16) float smem[];
     __shared__ int32_t s_slot[RT];
+    __shared__ int32_t s_oe[RT];                  // per-token results kept for the single-workgroup tail
+    __shared__ float s_og[RT], s_xn[RT];
     constexpr int EP = NEB * 32;
     constexpr int THREADS = NWR * 64;
     // reduction steps whose operands are fetched together, so that one memory
     // round trip feeds several MFMAs: bounded by registers (1 + 3*NEB loads per step)
     constexpr int G = NEB == 1 ? 8 : NEB == 2 ? 6 : NEB <= 5 ? 2 : 1;
-    float* part = smem;                           // [NWR waves][EP][RTP] partial logits
-    float* sqp = smem + NWR * EP * RTP;           // [NWR waves][2 halves][RT] partial sums of squares
+    constexpr int CP = RT * TB + 1;               // padded row of the partial-logit tile
+    float* part = smem;                           // [NWR waves][EP][CP] partial logits
+    float* sqp = smem + NWR * EP * CP;            // [NWR waves][2 halves][TB][RT] partial sums of squares
     __shared__ int32_t s_e2s[EP];
 
     // wave index as a scalar: loop bounds that guard MFMAs must be wave-uniform for the
     // compiler as well (an MFMA under a lane mask still runs for every lane)
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-    const int t0 = blockIdx.x * RT;
+    const int tw0 = blockIdx.x * RT * TB;         // first token of the workgroup
     for (int e = tid; e < EP; e += THREADS) s_e2s[e] = e < E ? e2s[e] : -1;
 
     const int nkb = d >> 4;
     const int per = (nkb + NWR - 1) / NWR;
     const int kb_lo = min(wave * per, nkb), kb_hi = min(kb_lo + per, nkb);
-    const int trow = min(t0 + (lane & 31), T - 1);
-    const uint16_t* xp = x + (size_t)trow * d + (lane >> 5) * 8;
+    const uint16_t* xp[TB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+        const int trow = min(tw0 + tb * RT + (lane & 31), T - 1);
+        xp[tb] = x + (size_t)trow * d + (lane >> 5) * 8;
+    }
     const uint4* wp = Wsplit + lane;
 
-    f32x16 acc[NEB];
+    f32x16 acc[NEB][TB];
+    float sq[TB];
 #pragma unroll
-    for (int b = 0; b < NEB; ++b)
+    for (int tb = 0; tb < TB; ++tb) {
+        sq[tb] = 0.f;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
-    float sq = 0.f;
+        for (int b = 0; b < NEB; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[b][tb][i] = 0.f;
+    }
 
     for (int g0 = kb_lo; g0 < kb_hi; g0 += G) {
-        uint4 xv[G];
+        uint4 xv[G][TB];
         uint4 w[G][NEB][3];
 #pragma unroll
         for (int i = 0; i < G; ++i) {
             const int kb = min(g0 + i, kb_hi - 1);            // past the end: reloaded, not used
-            xv[i] = *(const uint4*)(xp + kb * 16);
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) xv[i][tb] = *(const uint4*)(xp[tb] + kb * 16);
 #pragma unroll
             for (int b = 0; b < NEB; ++b)
 #pragma unroll
@@ -291,34 +306,48 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
         __builtin_amdgcn_sched_barrier(0);                    // all of the group's loads are issued first
 #pragma unroll
         for (int i = 0; i < G; ++i) {
-            // steps past the end of the range contribute a zero token operand
-            const uint4 xz = g0 + i < kb_hi ? xv[i] : make_uint4(0, 0, 0, 0);
-            uint32_t xw[4] = {xz.x, xz.y, xz.z, xz.w};
+            bf16x8 xf[TB];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float a = __uint_as_float(xw[q] << 16), c = __uint_as_float(xw[q] & 0xFFFF0000u);
-                sq = fmaf(a, a, sq);
-                sq = fmaf(c, c, sq);
+            for (int tb = 0; tb < TB; ++tb) {
+                // steps past the end of the range contribute a zero token operand
+                const uint4 xz = g0 + i < kb_hi ? xv[i][tb] : make_uint4(0, 0, 0, 0);
+                uint32_t xw[4] = {xz.x, xz.y, xz.z, xz.w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float a = __uint_as_float(xw[q] << 16), c = __uint_as_float(xw[q] & 0xFFFF0000u);
+                    sq[tb] = fmaf(a, a, sq[tb]);
+                    sq[tb] = fmaf(c, c, sq[tb]);
+                }
+                xf[tb] = frag_of(xz);
             }
-            bf16x8 xf = frag_of(xz);
             // smallest terms first, so they are not absorbed by the large partial sums
 #pragma unroll
             for (int s3 = 2; s3 >= 0; --s3)
 #pragma unroll
                 for (int b = 0; b < NEB; ++b)
-                    acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_of(w[i][b][s3]), xf, acc[b], 0, 0, 0);
+#pragma unroll
+                    for (int tb = 0; tb < TB; ++tb)
+                        acc[b][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_of(w[i][b][s3]), xf[tb], acc[b][tb],
+                                                                             0, 0, 0);
         }
     }
     // accumulator register i of lane l: expert 8*(i/4) + 4*(l/32) + i%4 (+32 per block), token l%32
 #pragma unroll
-    for (int b = 0; b < NEB; ++b)
+    for (int tb = 0; tb < TB; ++tb) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            int e = b * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-            part[(wave * EP + e) * RTP + (lane & 31)] = acc[b][i];
-        }
-    sqp[(wave * 2 + (lane >> 5)) * RT + (lane & 31)] = sq;
+        for (int b = 0; b < NEB; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                int e = b * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+                part[(wave * EP + e) * CP + tb * RT + (lane & 31)] = acc[b][tb][i];
+            }
+        sqp[((wave * 2 + (lane >> 5)) * TB + tb) * RT + (lane & 31)] = sq[tb];
+    }
     __syncthreads();
+
+    for (int tb = 0; tb < TB; ++tb) {                 // one 32-token block at a time through the epilogue
+    const int t0 = tw0 + tb * RT;
+    if (TB > 1 && t0 >= T) break;                     // uniform: the batch ended inside this workgroup
 
     // epilogue: lane l of wave w owns token l%32 and the experts j, j + 2*NWR, ... with
     // j = 2w + l/32, so a wave's LDS reads walk consecutive tokens (no bank conflicts) and
@@ -327,8 +356,6 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
     constexpr int EPL = EP / EG;                  // experts per lane
     __shared__ float s_best[NWR][RT], s_rbest[NWR][RT], s_z[NWR][RT], s_zr[NWR][RT];
     __shared__ int32_t s_bi[NWR][RT], s_rbi[NWR][RT];
-    __shared__ int32_t s_oe[RT];
-    __shared__ float s_og[RT], s_xn[RT];
     const int st = lane & 31, half = lane >> 5;
     // Everything below is written with selects, not branches: a compare-and-update under a
     // lane mask costs the wave a jump per candidate.  Experts past E carry -inf, which never
@@ -345,9 +372,9 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
 #pragma unroll
     for (int i = 0; i < EPL; ++i) {
         const int e = wave * 2 + half + EG * i;
-        float sum = part[e * RTP + st];
+        float sum = part[e * CP + tb * RT + st];
 #pragma unroll
-        for (int w = 1; w < NWR; ++w) sum += part[(w * EP + e) * RTP + st];   // fixed order
+        for (int w = 1; w < NWR; ++w) sum += part[(w * EP + e) * CP + tb * RT + st];   // fixed order
         res[i] = s_e2s[e] >= 0;                   // -1 past E as well
         v[i] = e < E ? sum : -INFINITY;
         better(v[i], e, best, bi);                // ascending e within the lane
@@ -389,7 +416,7 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
         for (int w = 1; w < NWR; ++w) { z += s_z[w][st]; zr += s_zr[w][st]; }
         float ss = 0.f;
 #pragma unroll
-        for (int q = 0; q < 2 * NWR; ++q) ss += sqp[q * RT + st];
+        for (int q = 0; q < 2 * NWR; ++q) ss += sqp[(q * TB + tb) * RT + st];
         const float ps = expf(rbest - best);
         orig_expert[tok] = bi;
         orig_gate[tok] = 1.0f / z;
@@ -407,10 +434,13 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
         for (int k = tid; k < K; k += THREADS) {
             int c = 0;
             for (int i = 0; i < n; ++i) c += s_slot[i] == k;
-            hist32[(size_t)blockIdx.x * K + k] = c;
+            hist32[((size_t)blockIdx.x * TB + tb) * K + k] = c;
         }
     }
-    if (!tail.perm) return;
+    if (TB > 1) __syncthreads();                      // the tables are reused by the next block
+    }
+    if (TB > 1 || !tail.perm) return;
+    const int t0 = tw0;
     // ---- single-workgroup tail (T <= RT, one workgroup): ranking and importance
     __shared__ int32_t s_cnt[256], s_off[256];
     for (int k = tid; k < 256; k += THREADS) s_cnt[k] = 0;
@@ -481,13 +511,13 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
     }
 }
 
-template <int NEB>
-int launch_mfma(const smoe_layer* L, const void* x, int T, int32_t* oe, float* og, int32_t* sl, float* g,
-                float* xn, int32_t* hist32, const TailArgs& tail, hipStream_t s) {
+template <int NEB, int TB>
+int launch_mfma_tb(const smoe_layer* L, const void* x, int T, int32_t* oe, float* og, int32_t* sl, float* g,
+                   float* xn, int32_t* hist32, const TailArgs& tail, hipStream_t s) {
     constexpr int EP = NEB * 32;
     constexpr int NWR = NEB <= 2 ? 8 : 4;
-    size_t lds = (size_t)(NWR * EP * RTP + 2 * NWR * RT) * 4;
-    auto kern = route_mfma_kernel<NEB, NWR>;
+    size_t lds = (size_t)(NWR * EP * (RT * TB + 1) + 2 * NWR * RT * TB) * 4;
+    auto kern = route_mfma_kernel<NEB, NWR, TB>;
     if (lds > 48 * 1024) {   // raise the kernel's dynamic-LDS limit once per device, not on every launch
         static int raised_on = -1;
         int dev_now = 0;
@@ -500,10 +530,22 @@ int launch_mfma(const smoe_layer* L, const void* x, int T, int32_t* oe, float* o
             raised_on = dev_now;
         }
     }
-    hipLaunchKernelGGL(kern, dim3((T + RT - 1) / RT), dim3(NWR * 64), lds, s, (const uint16_t*)x,
+    hipLaunchKernelGGL(kern, dim3((T + RT * TB - 1) / (RT * TB)), dim3(NWR * 64), lds, s, (const uint16_t*)x,
                        (const uint4*)L->d_router_split, L->d_expert_to_slot, T, L->cfg.d_model, L->cfg.E,
                        L->cfg.gate_mode, oe, og, sl, g, xn, hist32, L->cfg.K, tail);
     return smoe_check_hip(hipGetLastError(), "smoe_route launch");
+}
+
+template <int NEB>
+int launch_mfma(const smoe_layer* L, const void* x, int T, int32_t* oe, float* og, int32_t* sl, float* g,
+                float* xn, int32_t* hist32, const TailArgs& tail, hipStream_t s) {
+    // more 32-token blocks than compute units (256): two blocks per workgroup, while the partial-logit
+    // tile of 64 tokens still fits the LDS (up to 128 experts)
+    if constexpr (NEB <= 4) {
+        if ((T + RT - 1) / RT > 256 && !tail.perm)
+            return launch_mfma_tb<NEB, 2>(L, x, T, oe, og, sl, g, xn, hist32, tail, s);
+    }
+    return launch_mfma_tb<NEB, 1>(L, x, T, oe, og, sl, g, xn, hist32, tail, s);
 }
 
 template <typename XT, int NEC>

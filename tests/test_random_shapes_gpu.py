@@ -27,6 +27,9 @@ def _cases():
         out.append(dict(E=E, K=int(rng.integers(1, min(E, 24) + 1)), d=int(rng.choice([32, 64, 96, 160, 256, 384])),
                         f=int(rng.choice([32, 96, 224, 512, 1024])), T=Ts[i % len(Ts)], gate_mode=int(rng.integers(0, 2)),
                         residual=bool(rng.integers(0, 2)), perm_seed=int(rng.integers(1 << 30)), seed=3000 + i))
+    # more 32-token blocks than compute units: the router takes two blocks per workgroup
+    out.append(dict(E=16, K=5, d=64, f=96, T=8300, gate_mode=0, residual=True, perm_seed=11, seed=3100))
+    out.append(dict(E=100, K=9, d=96, f=64, T=8211, gate_mode=1, residual=False, perm_seed=12, seed=3101))
     return out
 
 
