@@ -220,7 +220,6 @@ __global__ __launch_bounds__(256) void split_router_kernel(const float* __restri
 }
 
 constexpr int RT = 32;            // tokens per workgroup
-constexpr int RTP = RT + 1;       // padded row of the partial-logit tile
 
 // A batch of at most RT tokens is one workgroup, which then holds every token's
 // result and can finish the step's ranking (smoe_permute's index part) and the
