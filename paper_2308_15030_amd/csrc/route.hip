@@ -219,7 +219,7 @@ __global__ __launch_bounds__(256) void split_router_kernel(const float* __restri
     dst[128] = make_uint4(lo[0] | lo[1] << 16, lo[2] | lo[3] << 16, lo[4] | lo[5] << 16, lo[6] | lo[7] << 16);
 }
 
-constexpr int RT = 32;            // tokens per workgroup
+constexpr int RT = 32;            // tokens per token block (one MFMA operand)
 
 // A batch of at most RT tokens is one workgroup, which then holds every token's
 // result and can finish the step's ranking (smoe_permute's index part) and the
