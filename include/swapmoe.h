@@ -83,11 +83,13 @@ const char* smoe_last_error(void);
  * FFN's hidden activations for max_tokens rows).  0 if layer is NULL. */
 size_t smoe_workspace_bytes(const smoe_layer_t* layer);
 
-/* Bytes of ONE of the two slot weight arrays (slot_w1 or slot_w2) for all K
- * slots.  The arrays are opaque to the caller: for SMOE_BF16 the library keeps
- * each slot in a tiled order that feeds the matrix cores with contiguous loads
- * (see smoe_set_resident), so they can only be filled through
- * smoe_set_resident.  Equals K * d_model * d_ff * sizeof(dtype). */
+/* Bytes of ONE of the two slot weight arrays (slot_w1 or slot_w2) for all
+ * K + spare_slots physical slots.  The arrays are opaque to the caller: for
+ * SMOE_BF16 the library keeps each slot in a tiled order that feeds the matrix
+ * cores with contiguous loads (see smoe_set_resident), so they can only be
+ * filled through smoe_set_resident / smoe_update_tick.
+ * Equals (K + spare_slots) * d_model * d_ff * sizeof(dtype): always size the
+ * arrays with this call, never with K alone. */
 size_t smoe_slot_weight_bytes(const smoe_layer_t* layer);
 
 /* Binds the caller-owned device buffers the layer works on.
@@ -113,8 +115,10 @@ int smoe_expert_norm(smoe_layer_t* layer, const void* w1, const void* w2, int n,
 
 /* Virtual-Expert update (Section 3.2): puts `expert` into `slot`.  Reads the
  * expert's weights in bank layout, w1_src [d_model, d_ff] and w2_src
- * [d_ff, d_model] (device memory, or pinned host memory mapped into the
- * device), and writes them into the slot arrays in the library's tiled order;
+ * [d_ff, d_model] (device memory, managed memory, or pinned host memory mapped
+ * into the device; pageable host memory is refused with SMOE_EINVAL before
+ * anything is launched), and writes them into the slot arrays in the library's
+ * tiled order;
  * updates the slot<->expert maps on the host and, in stream order, on the
  * device.  The previous occupant of the slot stops being resident.
  * Errors: slot outside [0,K) or expert outside [0,E) -> SMOE_EINVAL; expert
@@ -188,7 +192,9 @@ int smoe_expert_ffn(smoe_layer_t* layer, const void* x_perm, const int32_t* offs
  * and per-expert outputs of the individual calls
  * are produced: orig_expert, orig_gate, slot, gate, xnorm [T]; count, gsum,
  * score [E] (accumulate as in smoe_importance); perm, inv_perm [T];
- * offsets [K+1].  residual may be NULL and may alias x; out must not alias x. */
+ * offsets [K+1].  residual may be NULL and may alias x; out must not alias x.
+ * T = 0 leaves what the separate calls leave: offsets = 0 and, with
+ * accumulate = 0, zeroed count / gsum / score. */
 int smoe_forward(smoe_layer_t* layer, const void* x, int T, const void* residual, void* out,
                  int accumulate, int32_t* orig_expert, float* orig_gate, int32_t* slot, float* gate,
                  float* xnorm, int32_t* count, float* gsum, float* score, int32_t* perm,
@@ -217,7 +223,10 @@ int smoe_forward(smoe_layer_t* layer, const void* x, int T, const void* residual
  *   bank_w2 hold all E experts contiguously ([E][d_model][d_ff] and
  *   [E][d_ff][d_model], the layer's dtype) in device memory or in pinned host
  *   memory (then the copy engines bring the expert into a staging area of the
- *   workspace first); they must stay valid until the load is done.
+ *   workspace first); they must stay valid until the load is done.  Pageable
+ *   host memory is refused with SMOE_EINVAL before anything is launched.
+ *   A planned change whose slot still has an earlier load in flight waits
+ *   for that load's commit; the other changes go ahead of it.
  *   load_stream must differ from compute_stream for any overlap to happen.
  *   Returns the number of commits made by this call (>= 0) or a negative status.
  * smoe_update_pending: planned changes not yet committed (in flight included). */

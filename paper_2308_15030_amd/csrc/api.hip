@@ -4,6 +4,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <algorithm>
 #include <new>
@@ -19,6 +20,24 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 hipStream_t as_stream(void* s) { return (hipStream_t)s; }
 
 bool misaligned(const void* p, size_t a) { return ((uintptr_t)p % a) != 0; }
+
+// A weight source or bank is read by a kernel (or by the copy engines): it must be memory the
+// GPU can reach -- a device allocation, managed memory or pinned host memory.  A pageable host
+// pointer (malloc, a numpy array) would fault on the GPU, so it is turned away here, before
+// any launch.  *is_host (optional) tells pinned host memory from the rest.
+int check_gpu_readable(const void* p, const char* who, const char* what, bool* is_host = nullptr) {
+    hipPointerAttribute_t at;
+    hipError_t e = hipPointerGetAttributes(&at, p);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();                   // the failed query must not surface in a later call
+        return smoe_fail(SMOE_EINVAL, "%s: %s is not device, managed or pinned host memory (%s)", who, what,
+                         hipGetErrorString(e));
+    }
+    if (at.type != hipMemoryTypeDevice && at.type != hipMemoryTypeHost && at.type != hipMemoryTypeManaged)
+        return smoe_fail(SMOE_EINVAL, "%s: %s is not device, managed or pinned host memory", who, what);
+    if (is_host) *is_host = at.type == hipMemoryTypeHost;
+    return SMOE_OK;
+}
 }  // namespace
 
 int smoe_fail(int code, const char* fmt, ...) {
@@ -85,6 +104,12 @@ int smoe_create(const smoe_config* cfg, smoe_layer_t** out) {
     L->cfg = c;
     L->slot_to_expert.assign(c.K, -1);
     L->expert_to_slot.assign(c.E, -1);
+    // tuning aid, read once here and never on a hot call: SMOE_FFN_VARIANT="v1,v2" fixes the tile
+    // shapes of the two FFN products (indices checked by the launcher; anything else is ignored)
+    if (const char* env = getenv("SMOE_FFN_VARIANT")) {
+        int a = -1, b = -1;
+        if (sscanf(env, "%d,%d", &a, &b) == 2 && a >= 0 && b >= 0) { L->ffn_variant[0] = a; L->ffn_variant[1] = b; }
+    }
     *out = L;
     return SMOE_OK;
 }
@@ -115,8 +140,10 @@ int smoe_bind(smoe_layer_t* L, const float* router_w, void* slot_w1, void* slot_
         return smoe_fail(SMOE_EINVAL, "smoe_bind: null buffer");
     if (misaligned(slot_w1, 256) || misaligned(slot_w2, 256) || misaligned(workspace, 256))
         return smoe_fail(SMOE_EINVAL, "smoe_bind: slot arrays and workspace must be 256-byte aligned");
-    if (misaligned(router_w, 16) || misaligned(expert_norm, 4))
+    if (misaligned(router_w, 16))
         return smoe_fail(SMOE_EINVAL, "smoe_bind: router_w must be 16-byte aligned");
+    if (misaligned(expert_norm, 4))
+        return smoe_fail(SMOE_EINVAL, "smoe_bind: expert_norm must be 4-byte aligned");
     smoe_ws_layout w = smoe_ws_plan(L->cfg);
     L->router_w = router_w;
     L->slot_w1 = slot_w1;
@@ -144,6 +171,7 @@ int smoe_bind(smoe_layer_t* L, const float* router_w, void* slot_w1, void* slot_
     L->free_stage.clear();
     for (int i = L->cfg.spare_slots - 1; i >= 0; --i) L->free_stage.push_back(i);
     L->plan.clear();
+    L->bank_seen[0] = L->bank_seen[1] = nullptr;
     for (auto& st : L->staged) L->event_pool.push_back(st.done);   // loads of the old binding are forgotten
     L->staged.clear();
     L->slots_set = 0;
@@ -165,6 +193,10 @@ int smoe_expert_norm(smoe_layer_t* L, const void* w1, const void* w2, int n, flo
     if (!w1 || !w2 || !out) return smoe_fail(SMOE_EINVAL, "smoe_expert_norm: null buffer");
     if (misaligned(w1, 16) || misaligned(w2, 16))
         return smoe_fail(SMOE_EINVAL, "smoe_expert_norm: weights must be 16-byte aligned");
+    if (!L->bound) return smoe_fail(SMOE_ESTATE, "smoe_expert_norm: call smoe_bind first");
+    int rc = check_gpu_readable(w1, "smoe_expert_norm", "w1");
+    if (!rc) rc = check_gpu_readable(w2, "smoe_expert_norm", "w2");
+    if (rc) return rc;
     return smoe_launch_expert_norm(L, w1, w2, n, out, as_stream(stream));
 }
 
@@ -192,13 +224,16 @@ int smoe_set_resident(smoe_layer_t* L, int slot, int expert, const void* w1_src,
     int cur = L->expert_to_slot[expert];
     if (cur >= 0 && cur != slot)
         return smoe_fail(SMOE_ESTATE, "smoe_set_resident: expert %d is already resident in slot %d", expert, cur);
-    hipStream_t s = as_stream(stream);
-    int rc0 = ensure_workspace(L, s);
-    if (rc0) return rc0;
     for (const auto& st : L->staged)
         if (st.slot == slot || st.expert == expert)
             return smoe_fail(SMOE_ESTATE, "smoe_set_resident: slot %d / expert %d has an asynchronous load in flight",
                              st.slot, st.expert);
+    int rc0 = check_gpu_readable(w1_src, "smoe_set_resident", "w1_src");
+    if (!rc0) rc0 = check_gpu_readable(w2_src, "smoe_set_resident", "w2_src");
+    if (rc0) return rc0;
+    hipStream_t s = as_stream(stream);
+    rc0 = ensure_workspace(L, s);
+    if (rc0) return rc0;
     int old = L->slot_to_expert[slot];
     int map_done = 0;
     int rc = smoe_launch_pack_slot(L, L->phys[slot], w1_src, w2_src, s, slot, expert, old, &map_done);
@@ -270,12 +305,10 @@ int smoe_update_begin(smoe_layer_t* L, const float* score) {
     std::vector<int32_t> cs(L->cfg.K), ce(L->cfg.K);
     int n = plan_changes(L->cfg, score, s2e, e2s, cs.data(), ce.data());
     if (n < 0) return smoe_fail(SMOE_ESTATE, "smoe_update_begin: inconsistent maps");
+    // A slot whose load in flight is no longer wanted gets its new occupant after that load has
+    // been committed: the entry stays in the plan and smoe_update_tick holds it back until then.
     L->plan.clear();
-    for (int i = 0; i < n; ++i) {
-        bool busy = false;                       // a slot with a load in flight keeps what is coming
-        for (const auto& st : L->staged) busy |= st.slot == cs[i];
-        if (!busy) L->plan.emplace_back(cs[i], ce[i]);
-    }
+    for (int i = 0; i < n; ++i) L->plan.emplace_back(cs[i], ce[i]);
     return (int)L->plan.size();
 }
 
@@ -292,6 +325,17 @@ int smoe_update_tick(smoe_layer_t* L, const void* bank_w1, const void* bank_w2, 
     if (!bank_w1 || !bank_w2) return smoe_fail(SMOE_EINVAL, "smoe_update_tick: null bank");
     if (misaligned(bank_w1, 16) || misaligned(bank_w2, 16))
         return smoe_fail(SMOE_EINVAL, "smoe_update_tick: banks must be 16-byte aligned");
+    // the banks are read by a kernel or by the copy engines: checked once per pair of pointers
+    if (bank_w1 != L->bank_seen[0] || bank_w2 != L->bank_seen[1]) {
+        bool h1 = false, h2 = false;
+        int rc = check_gpu_readable(bank_w1, "smoe_update_tick", "bank_w1", &h1);
+        if (!rc) rc = check_gpu_readable(bank_w2, "smoe_update_tick", "bank_w2", &h2);
+        if (rc) return rc;
+        if (h1 != h2) return smoe_fail(SMOE_EINVAL, "smoe_update_tick: both banks must live in the same kind of memory");
+        L->bank_seen[0] = bank_w1;
+        L->bank_seen[1] = bank_w2;
+        L->bank_is_host = h1;
+    }
     hipStream_t ls = as_stream(load_stream), cs = as_stream(compute_stream);
     const smoe_config& c = L->cfg;
     if (L->released.empty()) L->released.assign(c.K + c.spare_slots, nullptr);
@@ -330,10 +374,14 @@ int smoe_update_tick(smoe_layer_t* L, const void* bank_w1, const void* bank_w2, 
     // A bank in host memory is brought over by the copy engines into the staging area and packed from
     // there: a kernel that reads host memory directly fills every CU's memory pipeline with slow PCIe
     // reads and slows the forward pass it is meant to overlap with.
-    int host_bank = -1;                                        // asked of the runtime only when a load starts
-    while (!L->plan.empty() && !L->free_phys.empty() && !L->free_stage.empty()) {
-        const int slot = L->plan.front().first, expert = L->plan.front().second;
-        L->plan.erase(L->plan.begin());
+    // The plan is walked in order; a change whose slot still has a load in flight waits for that
+    // load's commit (it stays in the plan) and the later changes go ahead of it.
+    for (size_t pi = 0; pi < L->plan.size() && !L->free_phys.empty() && !L->free_stage.empty();) {
+        const int slot = L->plan[pi].first, expert = L->plan[pi].second;
+        bool busy = false;
+        for (const auto& st : L->staged) busy |= st.slot == slot;
+        if (busy) { ++pi; continue; }
+        L->plan.erase(L->plan.begin() + pi);
         if (L->expert_to_slot[expert] >= 0) continue;          // became resident by another route
         smoe_layer::Staged st;
         st.slot = slot;
@@ -352,12 +400,7 @@ int smoe_update_tick(smoe_layer_t* L, const void* bank_w1, const void* bank_w2, 
             rc = smoe_check_hip(hipStreamWaitEvent(ls, L->released[st.phys], 0), "smoe_update_tick: stream order");
         const char* src1 = (const char*)bank_w1 + (size_t)expert * per;
         const char* src2 = (const char*)bank_w2 + (size_t)expert * per;
-        if (host_bank < 0) {
-            hipPointerAttribute_t at;
-            if (hipPointerGetAttributes(&at, bank_w1) == hipSuccess) host_bank = at.type == hipMemoryTypeHost;
-            else { (void)hipGetLastError(); host_bank = 0; }   // unregistered memory: treated as device-readable
-        }
-        if (!rc && host_bank == 1) {
+        if (!rc && L->bank_is_host) {
             char* s1 = L->d_stage + (size_t)st.stage * 2 * per;
             rc = smoe_check_hip(hipMemcpyAsync(s1, src1, per, hipMemcpyHostToDevice, ls), "smoe_update_tick: copy");
             if (!rc) rc = smoe_check_hip(hipMemcpyAsync(s1 + per, src2, per, hipMemcpyHostToDevice, ls),
@@ -459,7 +502,15 @@ int smoe_forward(smoe_layer_t* L, const void* x, int T, const void* residual, vo
         return smoe_fail(SMOE_EINVAL, "smoe_forward: only bf16 layers have the fused path; use the six calls");
     if (accumulate != 0 && accumulate != 1)
         return smoe_fail(SMOE_EINVAL, "smoe_forward: accumulate must be 0 or 1");
-    if (T == 0) return SMOE_OK;
+    if (T == 0) {   // what the separate calls leave behind for an empty batch: offsets = 0, and zeroed sums when overwriting
+        if (offsets) {
+            rc = smoe_launch_permute(L, nullptr, nullptr, 0, nullptr, nullptr, nullptr, offsets, as_stream(stream));
+            if (rc) return rc;
+        }
+        if (accumulate == 0 && count && gsum && score)
+            rc = smoe_launch_importance(L, nullptr, nullptr, nullptr, 0, count, gsum, score, 0, as_stream(stream));
+        return rc;
+    }
     if (!x || !out || !orig_expert || !orig_gate || !slot || !gate || !xnorm || !count || !gsum || !score ||
         !perm || !inv_perm || !offsets)
         return smoe_fail(SMOE_EINVAL, "smoe_forward: null buffer");

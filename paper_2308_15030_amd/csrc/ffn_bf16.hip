@@ -29,7 +29,6 @@
 // kernel runs as persistent workgroups that each walk a fixed share of the tiles.
 
 #include <algorithm>
-#include <cstdlib>
 #include <type_traits>
 
 #include "smoe_internal.h"
@@ -886,39 +885,36 @@ void launch_gemm(const uint16_t* X, const void* Wp, const int32_t* offsets, int 
                           (const uint4*)Wp, offsets, nslots, T, Y, R, N, fz);
 }
 
-constexpr int N_VARIANTS = 11;
+// the tile shapes launch_variant knows (every one of them is chosen somewhere by pick_variants)
+constexpr bool is_variant(int v) { return v == 1 || v == 3 || v == 4 || v == 5 || v == 6 || v == 8 || v == 10; }
 
 template <bool FIRST>
 void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* offsets, int nslots,
                     uint16_t* Y, int R, int N, int T, const FuseArgs& fz, hipStream_t s, hipEvent_t e0,
                     hipEvent_t e1) {
-    if (R % 64 != 0 && v != 5 && v != 6 && v != 9) {   // d_model / d_ff are multiples of 32 by contract: 32-deep slices always fit
+    if (R % 64 != 0 && v != 5 && v != 6) {   // d_model / d_ff are multiples of 32 by contract: 32-deep slices always fit
         launch_gemm<1, 4, 4, 32, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1);
         return;
     }
     switch (v) {             //            AF MAXB NW BKT PD OCC     tokens x features per workgroup
-        case 0: launch_gemm<2, 8, 4, 64, 1, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  // 256 x 256
         case 1: launch_gemm<1, 4, 4, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  // 128 x 128
-        case 2: launch_gemm<2, 2, 4, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  //  64 x 256
         case 3: launch_gemm<1, 2, 4, 64, 1, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  //  64 x 128
         case 4: launch_gemm<1, 1, 4, 64, 3, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  //  32 x 128
-        case 7: launch_gemm<2, 4, 4, 64, 3, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  // 128 x 256, one wave per SIMD
         case 8: launch_gemm<1, 4, 8, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  // 128 x 256, 8 waves
         case 10: launch_gemm<1, 8, 8, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break; // 256 x 256, 8 waves
         case 5: launch_small<4, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;   // 32 x 128, streaming
         case 6: launch_small<4, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;   // 32 x 32, reduction split 4 ways
-        case 9: launch_small<4, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;   // 32 x 64, split 2
         default: launch_small<4, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;
     }
 }
 
-// Tile shapes for the two GEMMs.  SMOE_FFN_VARIANT="v1,v2" overrides the
-// built-in choice (a tuning aid; the indices are those of launch_variant).
-void pick_variants(const smoe_config& c, int T, int& v1, int& v2) {
+// Tile shapes for the two GEMMs.  A pair fixed at smoe_create (SMOE_FFN_VARIANT="v1,v2", a
+// tuning aid; the indices are those of launch_variant) overrides the built-in choice.
+void pick_variants(const smoe_layer* L, int T, int& v1, int& v2) {
     // Thresholds measured on the Switch-base-64 shape (K = 16, 768 x 3072) over T = 48 .. 8192.
     // What decides in the middle range is whether the first product's tiles fit the chip in one
     // round (256-row tiles at 120-183 tokens per slot: one tile per slot and feature tile).
-    int per_slot = T / c.K;
+    int per_slot = T / L->cfg.K;
     if (per_slot >= 384) { v1 = 10; v2 = 1; }
     else if (per_slot >= 184) { v1 = 8; v2 = 1; }
     else if (per_slot >= 120) { v1 = 10; v2 = 3; }
@@ -926,13 +922,9 @@ void pick_variants(const smoe_config& c, int T, int& v1, int& v2) {
     else if (per_slot >= 28) { v1 = 3; v2 = 4; }
     else if (per_slot >= 6) { v1 = 4; v2 = 6; }
     else { v1 = 5; v2 = 6; }             // decode: a few tokens per slot, weight streaming
-    const char* env = getenv("SMOE_FFN_VARIANT");
-    if (env) {
-        int a = -1, b = -1;
-        if (sscanf(env, "%d,%d", &a, &b) == 2 && a >= 0 && b >= 0 && a < N_VARIANTS && b < N_VARIANTS) {
-            v1 = a;
-            v2 = b;
-        }
+    if (is_variant(L->ffn_variant[0]) && is_variant(L->ffn_variant[1])) {
+        v1 = L->ffn_variant[0];
+        v2 = L->ffn_variant[1];
     }
 }
 
@@ -942,7 +934,7 @@ int smoe_launch_ffn_bf16(const smoe_layer* L, const uint16_t* x_perm, const int3
                          uint16_t* y_perm, hipStream_t s) {
     const smoe_config& c = L->cfg;
     int v1, v2;
-    pick_variants(c, T, v1, v2);
+    pick_variants(L, T, v1, v2);
     uint16_t* h = (uint16_t*)L->d_hidden;
     const int32_t* phys = L->cfg.spare_slots > 0 ? L->d_phys : nullptr;   // identity without spare slots
     const FuseArgs none{phys, nullptr, nullptr, nullptr};
@@ -958,7 +950,7 @@ int smoe_launch_ffn_bf16_fused(const smoe_layer* L, const uint16_t* x, const int
                                const uint16_t* residual, int T, uint16_t* out, hipStream_t s) {
     const smoe_config& c = L->cfg;
     int v1, v2;
-    pick_variants(c, T, v1, v2);
+    pick_variants(L, T, v1, v2);
     uint16_t* h = (uint16_t*)L->d_hidden;
     const int32_t* phys = L->cfg.spare_slots > 0 ? L->d_phys : nullptr;   // identity without spare slots
     if (T <= 32 && v1 == 5 && v2 == 6) {      // the whole batch is one token block: no sorted tiles needed

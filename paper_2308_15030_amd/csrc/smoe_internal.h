@@ -34,6 +34,9 @@ struct smoe_layer {
     std::vector<int> free_stage;             // staging areas (one per spare slot) not in use
     char* d_stage = nullptr;                 // [spare_slots][2 matrices], bank layout: landing area of host-bank copies
     std::vector<hipEvent_t> released;        // per physical slot: compute-stream event after which it may be overwritten
+    const void* bank_seen[2] = {nullptr, nullptr};   // banks smoe_update_tick has validated
+    bool bank_is_host = false;               // ... and whether they are pinned host memory
+    int ffn_variant[2] = {-1, -1};           // SMOE_FFN_VARIANT read at smoe_create (tuning aid); -1: built-in choice
 
     // caller-owned device buffers
     const float* router_w = nullptr;

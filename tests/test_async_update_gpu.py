@@ -140,3 +140,80 @@ def test_asynchronous_update_state_rules():
     # a second plan replaces what has not started; a no-change plan is empty
     assert c.L.update_begin(score) == 0
     c.L.close()
+
+
+def test_new_plan_while_a_load_is_in_flight():
+    """A second plan arrives while the first plan's load is still staged, and its ranking no
+    longer wants the expert in flight: that slot's new occupant must not be lost -- it is loaded
+    once the earlier load has been committed -- so the final resident set is the update rule
+    (the oracle's select_resident) applied to the second plan's scores."""
+    cfg = wl.MoEConfig("async-replan", E=8, K=4, d_model=64, d_ff=96, T=40, dtype=wl.BF16, seed=6)
+    c = Case(cfg, bank_experts=range(cfg.E), spare_slots=1)
+    L = c.L
+    ls = torch.cuda.Stream()
+    score1 = np.array([0, 5, 4, 3, 9, 0, 0, 0], np.float32)      # wants 4, 1, 2, 3: expert 4 into slot 0
+    assert L.update_begin(score1) == 1
+    assert L.update_tick(c.d_W1, c.d_W2, ls) == 0                # the load of expert 4 is now in flight
+    assert L.update_pending() == 1
+    score2 = np.array([0, 5, 4, 3, 0, 9, 0, 0], np.float32)      # now wants 5, 1, 2, 3: slot 0 again
+    assert L.update_begin(score2) == 1                           # (slot 0, expert 5), behind the load in flight
+    assert L.update_pending() == 2
+    for _ in range(12):
+        ls.synchronize()
+        L.update_tick(c.d_W1, c.d_W2, ls)
+        if L.update_pending() == 0:
+            break
+    assert L.update_pending() == 0
+    s2e, e2s = L.maps()
+    # the oracle's rule on the second scores, from the maps after the first load's commit
+    s2e1 = np.array([4, 1, 2, 3], np.int32)
+    e2s1 = np.full(cfg.E, -1, np.int32); e2s1[s2e1] = np.arange(cfg.K)
+    want_s2e, want_e2s, _ = oracle.select_resident(score2.astype(np.float64), s2e1, e2s1)
+    assert np.array_equal(s2e, want_s2e) and np.array_equal(e2s, want_e2s)
+    assert s2e.tolist() == [5, 1, 2, 3]
+    out = L.forward_fused(c.d_x, c.T, accumulate=0)
+    ref = oracle.layer_forward(c.x, c.Wr, c.W1_bank[s2e], c.W2_bank[s2e], e2s)
+    torch.cuda.synchronize()
+    ok = ~ref["ambiguous"]
+    assert np.array_equal(to_host(L.slot)[ok], ref["slot"][ok])
+    assert max_abs_rel(values(to_host(out), cfg.dtype)[ok], values(ref["out"], cfg.dtype)[ok]) <= 2e-2
+    L.close()
+
+
+def test_pageable_host_memory_is_refused_before_any_launch():
+    """Weight sources and banks are read by kernels or by the copy engines: a numpy array
+    (pageable host memory) must come back as SMOE_EINVAL from the host-side check, with no
+    kernel launched; pinned host memory is accepted."""
+    cfg = wl.MoEConfig("ptr-check", E=6, K=2, d_model=64, d_ff=96, T=16, dtype=wl.BF16, seed=7)
+    c = Case(cfg, bank_experts=range(cfg.E), spare_slots=1)
+    L = c.L
+    w1, w2 = c.W1_bank, c.W2_bank                                # numpy, pageable
+    with pytest.raises(b.SmoeError) as e:
+        b.smoe_set_resident(L.handle, 0, 0, w1[0], w2[0])
+    assert e.value.status == b.SMOE_EINVAL
+    with pytest.raises(b.SmoeError) as e:
+        b.smoe_set_resident(L.handle, 0, 0, c.d_W1[0], w2[0])    # one good, one bad
+    assert e.value.status == b.SMOE_EINVAL
+    with pytest.raises(b.SmoeError) as e:
+        b.smoe_expert_norm(L.handle, w1, w2, cfg.E, L.expert_norm)
+    assert e.value.status == b.SMOE_EINVAL
+    L.update_begin(np.arange(cfg.E, dtype=np.float32))
+    ls = torch.cuda.Stream()
+    with pytest.raises(b.SmoeError) as e:
+        b.smoe_update_tick(L.handle, w1, w2, ls)
+    assert e.value.status == b.SMOE_EINVAL and L.update_pending() == 2       # nothing was started
+    # the refusals left no error behind in the runtime and changed no state
+    s2e, _ = L.maps()
+    assert s2e.tolist() == [0, 1]
+    p1 = torch.from_numpy(w1.view(np.int16)).pin_memory()
+    p2 = torch.from_numpy(w2.view(np.int16)).pin_memory()
+    L.set_resident(0, 0, p1[0], p2[0])                           # pinned host memory is a legal source
+    for _ in range(12):
+        ls.synchronize()
+        L.update_tick(p1, p2, ls)
+        if L.update_pending() == 0:
+            break
+    assert L.update_pending() == 0
+    torch.cuda.synchronize()
+    assert L.maps()[0].tolist() == [5, 4]
+    L.close()

@@ -351,6 +351,49 @@ def test_exact_tie_goes_to_lowest_index():
     np.testing.assert_allclose(r["orig_gate"][1], 0.25)
 
 
+def test_ambiguous_mask_written_out_by_hand():
+    """The near-tie mask: a token is ambiguous when the gap between the largest and the
+    second largest logit -- over all experts, or over the resident experts only -- is below
+    1e-4 * max(1, max_e |logit_e|).  The router is the identity here, so a token's logits
+    are its own coordinates, and the expected mask is worked out by hand for each row.
+    Experts 0 and 2 are resident."""
+    E = 4
+    Wr = np.eye(E, dtype=np.float32)
+    e2s = np.array([0, -1, 1, -1], np.int32)
+    rows = [
+        # logits                         ambiguous  why
+        ([0.5, 0.1, 0.2, 0.0],           False),  # every gap is large
+        ([0.5, 0.49993, 0.2, 0.0],       True),   # |logit| < 1 so the margin is 1e-4 (not 1e-4 * 0.5): global gap 7e-5
+        ([0.5, 0.49985, 0.2, 0.0],       False),  # global gap 1.5e-4 > 1e-4; resident gap 0.3
+        ([100.0, 99.995, 3.0, 2.0],      True),   # margin scales with max|logit|: 1e-2 > gap 5e-3
+        ([100.0, 99.98, 3.0, 2.0],       False),  # gap 2e-2 > 1e-2
+        ([0.5, 0.497, 0.1, -50.0],       True),   # the scale is max |logit| (here from a negative one): margin 5e-3 > gap 3e-3
+        ([0.5, 0.2, 0.1, -50.0],         False),
+        ([0.3, 0.9, 0.29996, 0.0],       True),   # only the resident pair (experts 0 and 2) is close: gap 4e-5
+        ([0.3, 0.29996, 0.1, 0.9],       False),  # a non-resident expert next to the resident best does not count;
+                                                  # the resident runner-up is expert 2, 0.2 away
+        ([0.9, 0.3, 0.1, 0.29996],       False),  # two close non-resident runners-up are no tie for the top
+        ([0.2, 0.9, 0.1, 0.89995],       True),   # only the global pair (both non-resident) is close
+    ]
+    x = np.array([r[0] for r in rows], np.float32)
+    want = np.array([r[1] for r in rows])
+    r = oracle.route(x, Wr, e2s)
+    assert r["ambiguous"].tolist() == want.tolist()
+    # the choices themselves are the plain arg-maxes (no near-tie changes them)
+    assert r["orig_expert"].tolist() == [0, 0, 0, 0, 0, 0, 0, 1, 3, 0, 1]
+    assert r["slot"].tolist() == [0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0]
+    # a custom margin is honoured: ten times wider flags row 2 (gap 1.5e-4 < 1e-3) as well
+    wide = oracle.route(x, Wr, e2s, margin=1e-3)["ambiguous"]
+    assert wide[2] and not wide[0]
+    # one resident expert: there is no resident runner-up, so only the global gap decides
+    one = np.array([-1, -1, 0, -1], np.int32)
+    r1 = oracle.route(x, Wr, one)
+    assert r1["ambiguous"].tolist() == [False, True, False, True, False, True, False, False, False, False, True]
+    # a single expert can never tie
+    r2 = oracle.route(x[:, :1].copy(), np.ones((1, 1), np.float32), np.array([0], np.int32))
+    assert not r2["ambiguous"].any()
+
+
 # --------------------------------------------------------------------- rounding
 def test_bf16_rounding_matches_torch():
     rng = np.random.default_rng(1)

@@ -85,11 +85,17 @@ def test_route(case):
     np.testing.assert_allclose(to_host(L.orig_gate)[ok], r["orig_gate"][ok], rtol=TOL_GATE)
     np.testing.assert_allclose(to_host(L.gate)[ok], r["gate"][ok], rtol=TOL_GATE)
     np.testing.assert_allclose(to_host(L.xnorm), r["xnorm"], rtol=TOL_GATE)
-    # ambiguous tokens must still pick one of the two near-tied experts
+    # ambiguous tokens must still pick one of the near-tied experts: the original choice within the
+    # margin of the largest logit, the served slot's expert resident and within the margin of the
+    # largest resident logit
     amb = np.nonzero(~ok)[0]
+    resident = c.e2s >= 0
     for t in amb:
         lg = r["logits"][t]
-        assert lg[to_host(L.orig_expert)[t]] >= lg.max() - oracle.MARGIN * max(1.0, np.abs(lg).max())
+        delta = oracle.MARGIN * max(1.0, np.abs(lg).max())
+        assert lg[to_host(L.orig_expert)[t]] >= lg.max() - delta
+        served = c.s2e[to_host(L.slot)[t]]
+        assert resident[served] and lg[served] >= lg[resident].max() - delta
 
 
 def test_importance(case):
