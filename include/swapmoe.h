@@ -171,6 +171,21 @@ int smoe_importance(smoe_layer_t* layer, const int32_t* orig_expert, const float
 int smoe_permute(smoe_layer_t* layer, const void* x, const int32_t* slot, int T, void* x_perm,
                  int32_t* perm, int32_t* inv_perm, int32_t* offsets, void* stream);
 
+/* smoe_permute for callers that cannot allocate device memory and have no
+ * workspace to bind -- code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same results bit for bit,
+ * but the sort's per-block histograms (its only device memory beyond inputs
+ * and outputs) live in a fixed 64-KiB array inside the library image, one copy
+ * per GPU for the life of the process; the handle need not be bound.  The call
+ * allocates nothing and synchronises nothing.
+ * Limit: T <= 65536 (and T <= max_tokens); more is refused with SMOE_EINVAL.
+ * Every call on a GPU shares that GPU's array: calls whose stream work may
+ * overlap on one GPU (different streams, no ordering) race and must be
+ * serialised by the caller.  Nothing in the array needs clearing between
+ * calls -- each call overwrites every entry it later reads. */
+int smoe_permute_static(smoe_layer_t* layer, const void* x, const int32_t* slot, int T, void* x_perm,
+                        int32_t* perm, int32_t* inv_perm, int32_t* offsets, void* stream);
+
 /* Grouped expert FFN, E_i(x) of the Background section: rows
  * [offsets[k], offsets[k+1]) of x_perm [T, d_model] belong to slot k and get
  *   y_perm[r, :] = ReLU(x_perm[r, :] . W1_k) . W2_k          (no biases)

@@ -54,6 +54,7 @@ _SIGS = {
     "smoe_route": (C.c_int, [_vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp]),
     "smoe_importance": (C.c_int, [_vp, _vp, _vp, _vp, _i, _vp, _vp, _vp, _i, _vp]),
     "smoe_permute": (C.c_int, [_vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp]),
+    "smoe_permute_static": (C.c_int, [_vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp]),
     "smoe_expert_ffn": (C.c_int, [_vp, _vp, _vp, _i, _vp, _vp]),
     "smoe_combine": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _i, _vp, _vp]),
     "smoe_set_profile_events": (C.c_int, [_vp, _vp, _vp, _vp, _vp]),
@@ -148,6 +149,11 @@ def smoe_importance(layer, orig_expert, orig_gate, xnorm, T, count, gsum, score,
 def smoe_permute(layer, x, slot, T, x_perm, perm, inv_perm, offsets, stream=None):
     _check(_lib.smoe_permute(layer, _ptr(x), _ptr(slot), T, _ptr(x_perm), _ptr(perm), _ptr(inv_perm),
                              _ptr(offsets), _stream(stream)))
+
+
+def smoe_permute_static(layer, x, slot, T, x_perm, perm, inv_perm, offsets, stream=None):
+    _check(_lib.smoe_permute_static(layer, _ptr(x), _ptr(slot), T, _ptr(x_perm), _ptr(perm), _ptr(inv_perm),
+                                    _ptr(offsets), _stream(stream)))
 
 
 def smoe_expert_ffn(layer, x_perm, offsets, T, y_perm, stream=None):

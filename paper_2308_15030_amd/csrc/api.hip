@@ -476,6 +476,23 @@ int smoe_permute(smoe_layer_t* L, const void* x, const int32_t* slot, int T, voi
     return smoe_launch_permute(L, x, slot, T, x_perm, perm, inv_perm, offsets, as_stream(stream));
 }
 
+int smoe_permute_static(smoe_layer_t* L, const void* x, const int32_t* slot, int T, void* x_perm,
+                        int32_t* perm, int32_t* inv_perm, int32_t* offsets, void* stream) {
+    // needs the handle's shape only: no bound workspace, so an unbound handle is fine
+    if (!L) return smoe_fail(SMOE_EINVAL, "smoe_permute_static: null handle");
+    if (T < 0 || T > L->cfg.max_tokens)
+        return smoe_fail(SMOE_EINVAL, "smoe_permute_static: T=%d outside [0,%d]", T, L->cfg.max_tokens);
+    if (T > smoe_static_max_tokens())
+        return smoe_fail(SMOE_EINVAL, "smoe_permute_static: T=%d exceeds the %d tokens the library's fixed scratch "
+                         "array is sized for; use smoe_permute with a bound workspace", T, smoe_static_max_tokens());
+    if (!offsets) return smoe_fail(SMOE_EINVAL, "smoe_permute_static: null offsets");
+    if (T > 0 && (!x || !slot || !x_perm || !perm || !inv_perm))
+        return smoe_fail(SMOE_EINVAL, "smoe_permute_static: null buffer");
+    if (T > 0 && (misaligned(x, 16) || misaligned(x_perm, 16)))
+        return smoe_fail(SMOE_EINVAL, "smoe_permute_static: x and x_perm must be 16-byte aligned");
+    return smoe_launch_permute_static(L->cfg, x, slot, T, x_perm, perm, inv_perm, offsets, as_stream(stream));
+}
+
 int smoe_expert_ffn(smoe_layer_t* L, const void* x_perm, const int32_t* offsets, int T, void* y_perm,
                     void* stream) {
     int rc = check_hot(L, T, "smoe_expert_ffn", true);

@@ -94,6 +94,10 @@ int smoe_launch_importance(const smoe_layer* L, const int32_t* orig_expert, cons
                            int accumulate, hipStream_t s);
 int smoe_launch_permute(const smoe_layer* L, const void* x, const int32_t* slot, int T, void* x_perm,
                         int32_t* perm, int32_t* inv_perm, int32_t* offsets, hipStream_t s);
+// smoe_permute without a workspace: block histograms in the library's own fixed device array
+int smoe_static_max_tokens();
+int smoe_launch_permute_static(const smoe_config& c, const void* x, const int32_t* slot, int T, void* x_perm,
+                               int32_t* perm, int32_t* inv_perm, int32_t* offsets, hipStream_t s);
 int smoe_launch_ffn_f32(const smoe_layer* L, const float* x_perm, const int32_t* offsets, int T,
                         float* y_perm, hipStream_t s);
 int smoe_launch_ffn_bf16(const smoe_layer* L, const uint16_t* x_perm, const int32_t* offsets, int T,

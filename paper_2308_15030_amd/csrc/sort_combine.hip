@@ -11,6 +11,8 @@
 //  * combine: out[t] = gate[t] * y_perm[inv_perm[t]] (+ residual); top-1 means
 //    one source row per token, so this is a gather with 16-byte accesses.
 
+#include <mutex>
+
 #include "smoe_internal.h"
 
 namespace {
@@ -345,6 +347,69 @@ int smoe_launch_permute(const smoe_layer* L, const void* x, const int32_t* slot,
                            (const uint4*)x, perm, T, cpr, (uint4*)x_perm);
     }
     return smoe_check_hip(hipGetLastError(), "smoe_permute launch");
+}
+
+// ---------------------------------------------------------------------------
+// smoe_permute for callers that may not allocate and have no workspace to bind:
+// the per-block slot histograms, the one piece of device memory the sort needs
+// beyond its inputs and outputs, live in a fixed array inside the library
+// image instead of the bound workspace.  Every GPU the library runs on holds
+// its own copy of the array (64 KiB) from the moment the code object is loaded
+// until the process ends, at an address of its own, which is asked of the
+// runtime once per device; host code never uses the array's name for anything
+// else (the name is a host-side stand-in, not a device address).
+constexpr int STATIC_MAX_TOKENS = 65536;                         // 64 sort blocks
+constexpr int STATIC_MAX_SLOTS = 256;                            // K <= E <= 256 by the C ABI
+constexpr int STATIC_HIST_INTS = (STATIC_MAX_TOKENS / SMOE_SORT_BLOCK) * STATIC_MAX_SLOTS;
+static __device__ __align__(256) int32_t scratch[STATIC_HIST_INTS];
+
+constexpr int MAX_DEVICES = 64;
+static int32_t* g_scratch_ptr[MAX_DEVICES];                      // device address of `scratch`, per device
+static std::mutex g_scratch_mu;
+
+// Address of this device's copy of the array (the current device), or an error.
+static int static_scratch(int32_t** out) {
+    int dev = -1;
+    int rc = smoe_check_hip(hipGetDevice(&dev), "smoe_permute_static: current device");
+    if (rc) return rc;
+    if (dev < 0 || dev >= MAX_DEVICES)
+        return smoe_fail(SMOE_EINVAL, "smoe_permute_static: device index %d outside [0,%d)", dev, MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        rc = smoe_check_hip(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "smoe_permute_static: scratch address");
+        if (rc) return rc;
+        if (!p) return smoe_fail(SMOE_EHIP, "smoe_permute_static: the runtime returned no address for the scratch array");
+        g_scratch_ptr[dev] = (int32_t*)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return SMOE_OK;
+}
+
+int smoe_static_max_tokens() { return STATIC_MAX_TOKENS; }
+
+// Same three launches as smoe_launch_permute; only the histogram buffer differs.  Nothing in
+// the array has to start at zero: the histogram launch overwrites every entry the ranking
+// launch reads ([blocks of this call][K]), so a smaller call after a larger one is safe.
+int smoe_launch_permute_static(const smoe_config& c, const void* x, const int32_t* slot, int T, void* x_perm,
+                               int32_t* perm, int32_t* inv_perm, int32_t* offsets, hipStream_t s) {
+    const int K = c.K;
+    const int nblk = T > 0 ? smoe_sort_blocks(T) : 1;
+    int32_t* hist = nullptr;
+    if (nblk > 1) {
+        int rc = static_scratch(&hist);
+        if (rc) return rc;
+        hipLaunchKernelGGL(sort_hist_kernel, dim3(nblk), dim3(SB), K * sizeof(int32_t), s, slot, T, K, hist);
+    }
+    hipLaunchKernelGGL(sort_rank_kernel, dim3(nblk), dim3(SB), (2 + SB_WAVES) * K * sizeof(int32_t), s,
+                       slot, T, K, nblk, hist, perm, inv_perm, offsets);
+    if (T > 0) {
+        int cpr = (int)((size_t)c.d_model * smoe_elem_size(c.dtype) / 16);
+        size_t total = (size_t)T * cpr;
+        hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                           (const uint4*)x, perm, T, cpr, (uint4*)x_perm);
+    }
+    return smoe_check_hip(hipGetLastError(), "smoe_permute_static launch");
 }
 
 int smoe_launch_rank_importance(const smoe_layer* L, const int32_t* orig_expert, const float* orig_gate,
