@@ -46,12 +46,44 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_MFMA_TFLOPS = 2500.0      # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per grouped-GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on
-# the default command (profiles/grouped_gemm_bf16_c3_prefill_hbm_counters.txt), mean of the two
-# launches of one FFN; None for any other configuration.
-MEASURED_TRAFFIC_C3 = 144.6e6
-# the same for the decode products (profiles/dense_gemm_bf16_c4_decode_hbm_counters.txt), default c4 run
-MEASURED_TRAFFIC_C4 = 67.0e6
+# HBM-side traffic of the dominant kernels is not measured live (it needs two rocprofv3 --pmc runs);
+# `roofline.traffic` is read from the committed counter summary of the same command, and only if
+# that summary names the kernel instances this run has just timed (smoe_describe_ffn).
+PROFILE_FILES = {
+    "c3": "profiles/grouped_gemm_bf16_c3_prefill_hbm_counters.txt",
+    "c4": "profiles/dense_gemm_bf16_c4_decode_hbm_counters.txt",
+    "c5": "profiles/grouped_gemm_bf16_c5_prefill_hbm_counters.txt",
+}
+
+
+def stored_traffic(workload, kernels_now):
+    """(bytes per launch or None, note).  The summary carries two machine-readable lines:
+    `bench.roofline.kernels = <first> | <second>` and `bench.roofline.traffic_bytes_per_launch = <n>`."""
+    path = os.path.join(ROOT, PROFILE_FILES.get(workload, ""))
+    if not os.path.isfile(path):
+        return None, "no counter summary for this workload under profiles/"
+    keys = {}
+    for line in open(path):
+        if line.startswith("bench.roofline.") and "=" in line:
+            k, v = line.split("=", 1)
+            keys[k.strip()] = v.strip()
+    kernels = keys.get("bench.roofline.kernels")
+    if kernels != kernels_now:
+        return None, f"{PROFILE_FILES[workload]} was collected with other kernels ({kernels}); re-collect it"
+    try:
+        return float(keys["bench.roofline.traffic_bytes_per_launch"]), PROFILE_FILES[workload]
+    except (KeyError, ValueError):
+        return None, f"{PROFILE_FILES[workload]} holds no traffic figure"
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def dev_t(a, dev):
@@ -164,6 +196,9 @@ def main():
     ap.add_argument("--per-call", action="store_true",
                     help="instead of the throughput run: median time of each of the five hot calls (and of "
                          "smoe_forward) over 100 iterations after 10 warm-ups, with the bytes and flops each moves")
+    ap.add_argument("--layers", type=int, default=None,
+                    help="prefill workloads: number of stacked layers (default: the workload's own; 1 keeps one "
+                         "layer's weights cache-resident between steps, a tuning aid)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--separate-calls", action="store_true",
                     help="drive the layer through the five per-step calls instead of smoe_forward")
@@ -188,7 +223,7 @@ def main():
     steps = args.steps if args.steps is not None else (cfg.steps if decode else 50)
     warmup = args.warmup if args.warmup is not None else (16 if decode else 10)
     T = cfg.T
-    L = args.decode_layers if decode else cfg.layers
+    L = args.decode_layers if decode else (args.layers or cfg.layers)
     s2e0, e2s0 = wl.initial_resident(cfg)
     use_events = not args.no_events
 
@@ -255,18 +290,15 @@ def main():
 
         if args.policy == "lru" and args.updates != "sync":
             sys.exit("bench.py: --policy lru needs --updates sync")
-        if args.policy == "static":
+        if args.policy == "static":                  # the K experts of largest |E_i|, chosen once by the library's policy unit
             args.updates = "none"
-            for lay, (d1, d2) in zip(layers, banks):           # resident set = the K largest experts by |E_i|
-                top = torch.argsort(lay.expert_norm, descending=True)[:cfg.K].cpu().tolist()
-                lay.rebind()
-                for sl, ex in enumerate(top):
+            for lay, (d1, d2) in zip(layers, banks):
+                for sl, ex in lay.select_resident(lay.policy_rank(b.SMOE_POLICY_MAGNITUDE)):
                     lay.set_resident(sl, ex, d1[ex], d2[ex])
             torch.cuda.synchronize()
         load_stream = torch.cuda.Stream()
         oe_log = torch.zeros(steps, T, dtype=torch.int32, device=dev) if args.hit_rate else None
         e2s_log = np.zeros((steps, cfg.E), np.int32)
-        last_use = [np.zeros(cfg.K, np.int64) for _ in layers]    # lru: step of each slot's last use
 
         graphs = {}
         x_in = torch.empty(T, cfg.d_model, dtype=xs.dtype, device=dev)
@@ -290,8 +322,9 @@ def main():
             torch.cuda.current_stream().wait_stream(side)
             torch.cuda.synchronize()
 
-        def rank_tensor(lay):
+        def rank_tensor(lay):                        # asynchronous path: the ranking numbers as a device tensor
             return lay.count.to(torch.float32) if args.policy == "count" else lay.score
+        lib_policy = b.SMOE_POLICY_COUNT if args.policy == "count" else b.SMOE_POLICY_IMPORTANCE
         n_samples = (steps + ev_stride - 1) // ev_stride
         offs_log = torch.zeros(n_samples, cfg.K + 1, dtype=torch.int32, device=dev)   # offsets of the timed launches
         score_host = [torch.zeros(cfg.E, dtype=torch.float32).pin_memory() for _ in layers]
@@ -326,17 +359,10 @@ def main():
                     if timed and args.hit_rate and l == 0:
                         oe_log[i].copy_(lay.orig_expert, non_blocking=True)
                         e2s_log[i] = lay.maps()[1]
-                    if args.policy == "lru":                       # load what was missed, evict the stalest slots
-                        oe = lay.orig_expert.cpu().numpy()
-                        s2e, e2s = lay.maps()
-                        used = e2s[oe]
-                        last_use[l][used[used >= 0]] = sidx + 1
-                        missed, cnt = np.unique(oe[used < 0], return_counts=True)
+                    if args.policy == "lru":         # load on miss: the library's plan (least recently used slots go)
                         d1, d2 = banks[l]
-                        victims = [int(v) for v in np.argsort(last_use[l], kind="stable") if last_use[l][v] <= sidx]
-                        for ex, sl in zip(missed[np.argsort(-cnt, kind="stable")], victims):
-                            lay.set_resident(sl, int(ex), d1[int(ex)], d2[int(ex)])
-                            last_use[l][sl] = sidx + 1
+                        for sl, ex in lay.on_demand_plan(T):
+                            lay.set_resident(sl, ex, d1[ex], d2[ex])
                             swaps += 1
                 if ahead > 0:
                     step_done[i % (ahead + 1)].record()
@@ -349,7 +375,7 @@ def main():
                             score_ev[l].record()
                             score_due[l] = True
                         else:
-                            score = rank_tensor(lay).cpu().numpy()   # the one host read-back per period
+                            score = lay.policy_rank(lib_policy)      # the one host read-back per period
                             for sl, ex in lay.select_resident(score):
                                 lay.set_resident(sl, ex, d1[ex], d2[ex])
                                 swaps += 1
@@ -373,6 +399,7 @@ def main():
     value = T * L / (dt / steps)
 
     roof = None
+    kernels_now = b.smoe_describe_ffn(layers[0].handle, T, not args.separate_calls)
     if use_events:
         g1 = np.array([evs[i][0].elapsed_time(evs[i][1]) for i in ev_used]) * 1e-3
         g2 = np.array([evs[i][2].elapsed_time(evs[i][3]) for i in ev_used]) * 1e-3
@@ -380,14 +407,21 @@ def main():
         if not decode:
             flops = 2.0 * T * cfg.d_model * cfg.d_ff           # per launch; two launches per FFN
             achieved = flops / avg / 1e12
-            bytes_launch = 2.0 * (cfg.K * cfg.d_model * cfg.d_ff + T * cfg.d_model + T * cfg.d_ff)
-            roof = {"bound": "mfma", "kernel": "grouped_gemm_bf16 (mean of the FFN's two launches)",
+            # algorithmic bytes per launch: the resident weights of one matrix per slot once, the
+            # tokens in and the layer output out (half of each per launch); the hidden activations'
+            # round trip through memory is the kernel's own doing and is listed separately
+            bytes_launch = 2.0 * (cfg.K * cfg.d_model * cfg.d_ff + T * cfg.d_model)
+            bytes_with_h = bytes_launch + 2.0 * T * cfg.d_ff
+            default_run = (not args.separate_calls and args.layers is None)
+            traffic, traffic_src = stored_traffic(args.workload, kernels_now) if default_run else (None, "non-default run")
+            roof = {"bound": "mfma", "kernel": kernels_now + " (mean of the FFN's two launches)",
                     "achieved": round(achieved, 2), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 4),
-                    "traffic": MEASURED_TRAFFIC_C3 if args.workload == "c3" else None,
+                    "traffic": traffic, "traffic_source": traffic_src,
                     "us_per_launch": round(avg * 1e6, 2), "us_gemm1": round(g1.mean() * 1e6, 2),
                     "us_gemm2": round(g2.mean() * 1e6, 2), "launches_timed": 2 * len(ev_used), "flop_per_launch": flops,
                     "hbm_bytes_per_launch_algorithmic": bytes_launch,
+                    "hbm_bytes_per_launch_with_hidden_round_trip": bytes_with_h,
                     "hbm_GBs": round(bytes_launch / avg / 1e9, 1),
                     "hbm_frac": round(bytes_launch / avg / 1e9 / PEAK_HBM_GBS, 4)}
         else:
@@ -397,9 +431,10 @@ def main():
                           and args.decode_layers == 1)
             bytes_launch = 2.0 * act * cfg.d_model * cfg.d_ff  # one weight matrix of every active slot
             achieved = bytes_launch / avg / 1e9
-            roof = {"bound": "hbm", "kernel": "dense_gemm_bf16 / small_gemm_bf16 (mean of the FFN's two launches)",
+            traffic, traffic_src = stored_traffic(args.workload, kernels_now) if default_c4 else (None, "non-default run")
+            roof = {"bound": "hbm", "kernel": kernels_now + " (mean of the FFN's two launches)",
                     "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": MEASURED_TRAFFIC_C4 if default_c4 else None,
+                    "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": traffic, "traffic_source": traffic_src,
                     "us_per_launch": round(avg * 1e6, 2), "us_gemm1": round(g1.mean() * 1e6, 2),
                     "us_gemm2": round(g2.mean() * 1e6, 2), "launches_timed": 2 * len(ev_used),
                     "mean_active_slots": round(act, 2),
@@ -416,7 +451,7 @@ def main():
                 oracle.layer_forward(x_host, Wr, W1[:cfg.K], W2[:cfg.K], e2s0)
             tc = time.perf_counter() - t1
             cpu = {"value": round(T * reps / tc, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
-                   "kind": "oracle", "sample": f"{reps} x one full layer (layer 0) of {cfg.name}, all {T} tokens "
+                   "cpu_model": cpu_model(), "kind": "oracle", "sample": f"{reps} x one full layer (layer 0) of {cfg.name}, all {T} tokens "
                                                f"each, {tc:.2f}s wall"}
         else:
             n = min(steps, 64)
@@ -425,7 +460,7 @@ def main():
                 oracle.layer_forward(xs_host[i], Wr, W1[:cfg.K], W2[:cfg.K], e2s0)
             tc = time.perf_counter() - t1
             cpu = {"value": round(T * n / tc, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
-                   "kind": "oracle", "sample": f"{n} decode steps of layer 0 of {cfg.name} on the initial "
+                   "cpu_model": cpu_model(), "kind": "oracle", "sample": f"{n} decode steps of layer 0 of {cfg.name} on the initial "
                                                f"resident set (no updates), {tc:.2f}s wall"}
 
     config = {"workload": cfg.name, "E": cfg.E, "K": cfg.K, "d_model": cfg.d_model, "d_ff": cfg.d_ff,

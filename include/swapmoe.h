@@ -142,6 +142,33 @@ int smoe_get_maps(const smoe_layer_t* layer, int32_t* slot_to_expert /*host*/,
 int smoe_select_resident(const smoe_layer_t* layer, const float* score /*host*/,
                          int32_t* changed_slots /*host*/, int32_t* changed_experts /*host*/);
 
+/* What ranks the experts at an update, for smoe_select_resident / smoe_update_begin:
+ *   SMOE_POLICY_IMPORTANCE  the Eq. 1 score (SwapMoE's own scheduling)
+ *   SMOE_POLICY_COUNT       the number of tokens routed to the expert, the "simple
+ *                           scheduling" of the ablation (Section 4.5)
+ *   SMOE_POLICY_MAGNITUDE   |E_i|, constant over time: the "Pruning" baseline of the
+ *                           evaluation (Section 4.1) keeps the K largest experts and never swaps
+ * Writes rank[e] (host, [E]) from the host copies of the layer's accumulators
+ * (count, score as smoe_importance leaves them) or of expert_norm; only the
+ * array the policy reads must be non-NULL. */
+enum { SMOE_POLICY_IMPORTANCE = 0, SMOE_POLICY_COUNT = 1, SMOE_POLICY_MAGNITUDE = 2 };
+int smoe_policy_scores(int policy, int E, const int32_t* count /*host*/, const float* score /*host*/,
+                       const float* expert_norm /*host*/, float* rank /*host*/);
+
+/* The "On demand" baseline (Section 4.1; the caching the paper's Section 2.1
+ * measures): after a batch, every expert that a token asked for and that was
+ * not resident is loaded, into the slots that have gone unused the longest.
+ * Reading (the paper gives no rule): given the batch's orig_expert [T] (host),
+ * slots whose expert was some token's own choice are stamped as used now; the
+ * missed experts, most requested first (ties: lower id), are paired with the
+ * slots not used by this batch, least recently used first (ties: lower slot),
+ * until either list ends.  The pairs are written to changed_slots /
+ * changed_experts (host, capacity K) and their number is returned; the caller
+ * loads them with smoe_set_resident.  The use stamps live in the handle and
+ * start afresh at smoe_bind. */
+int smoe_on_demand_plan(smoe_layer_t* layer, const int32_t* orig_expert /*host*/, int T,
+                        int32_t* changed_slots /*host*/, int32_t* changed_experts /*host*/);
+
 /* Router (Background section: with k = 1 only the expert with the largest G(x)_i runs)
  * and Masked Gating (Section 3.1).  For each token t of x [T, d_model]:
  *   logit = x_t . router_w^T (fp32), p = softmax(logit) over all E;
@@ -249,16 +276,6 @@ int smoe_update_begin(smoe_layer_t* layer, const float* score /*host, [E]*/);
 int smoe_update_tick(smoe_layer_t* layer, const void* bank_w1, const void* bank_w2, void* load_stream,
                      void* compute_stream);
 int smoe_update_pending(const smoe_layer_t* layer);
-
-/* Measurement aid (not part of the paper's method): HIP events for the NEXT
- * smoe_expert_ffn (or smoe_forward) call on this handle.  The call attaches
- * them to its two product kernels' own dispatches: g1_begin / g1_end take the
- * start and end of the first product's execution, g2_begin / g2_end those of
- * the second, so hipEventElapsedTime(g1_begin, g1_end) is that kernel's
- * duration with no launch gap in it.  The events are caller-owned hipEvent_t
- * values passed as void*; they are used once and then forgotten.  Pass four
- * NULLs to cancel. */
-int smoe_set_profile_events(smoe_layer_t* layer, void* g1_begin, void* g1_end, void* g2_begin, void* g2_end);
 
 /* Gate-weighted combine, y = G(x)_i E_i(x) in token order:
  *   out[t, :] = gate[t] * y_perm[inv_perm[t], :]  (+ residual[t, :] if not NULL)

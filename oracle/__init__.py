@@ -35,6 +35,8 @@ def lib():
         _lib.oracle_expert_ffn.restype = C.c_int
         _lib.oracle_combine.restype = C.c_int
         _lib.oracle_select_resident.restype = C.c_int
+        _lib.oracle_policy_scores.restype = C.c_int
+        _lib.oracle_on_demand.restype = C.c_int
         _lib.oracle_round_bf16.restype = None
         _lib.oracle_num_threads.restype = C.c_int
     return _lib
@@ -170,6 +172,38 @@ def select_resident(score, slot_to_expert, expert_to_slot):
     if n < 0:
         raise ValueError(f"oracle_select_resident rc={n}")
     return s2e, e2s, [(int(cs[i]), int(ce[i])) for i in range(n)]
+
+
+POLICY_IMPORTANCE, POLICY_COUNT, POLICY_MAGNITUDE = 0, 1, 2
+
+
+def policy_scores(policy, count, score, expert_norm_):
+    """What ranks the experts at an update under `policy` (float64 [E])."""
+    count = _c(count, np.int32); score = _c(score, np.float64); en = _c(expert_norm_, np.float64)
+    rank = np.empty(en.shape[0], np.float64)
+    rc = lib().oracle_policy_scores(int(policy), en.shape[0], _p(count), _p(score), _p(en), _p(rank))
+    if rc:
+        raise ValueError(f"oracle_policy_scores rc={rc}")
+    return rank
+
+
+class OnDemand:
+    """State of the load-on-miss baseline: a batch counter and per-slot use stamps."""
+
+    def __init__(self, K):
+        self.clock = np.zeros(1, np.int64)
+        self.last_use = np.zeros(K, np.int64)
+
+    def plan(self, orig_expert, expert_to_slot):
+        """[(slot, expert), ...] to load after a batch with these original choices."""
+        oe = _c(orig_expert, np.int32); e2s = _c(expert_to_slot, np.int32)
+        K = self.last_use.shape[0]
+        cs = np.empty(K, np.int32); ce = np.empty(K, np.int32)
+        n = lib().oracle_on_demand(_p(oe), oe.shape[0], e2s.shape[0], K, _p(e2s), _p(self.clock),
+                                   _p(self.last_use), _p(cs), _p(ce))
+        if n < 0:
+            raise ValueError(f"oracle_on_demand rc={n}")
+        return [(int(cs[i]), int(ce[i])) for i in range(n)]
 
 
 def num_threads() -> int:

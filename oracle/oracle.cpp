@@ -328,6 +328,61 @@ int oracle_select_resident(const double* score, int E, int K, int32_t* slot_to_e
     return n;
 }
 
+// The rankings the paper's evaluation compares, as inputs to the update rule above:
+//   policy 0  SwapMoE's own scheduling: the Eq. 1 importance score
+//   policy 1  "simple scheduling" (Section 4.5): the number of tokens dispatched to the expert
+//   policy 2  the "Pruning" baseline (Section 4.1): the expert's magnitude |E_i|, fixed
+int oracle_policy_scores(int policy, int E, const int32_t* count, const double* score,
+                         const double* expert_norm, double* rank) {
+    for (int e = 0; e < E; ++e) {
+        if (policy == 0) rank[e] = score[e];
+        else if (policy == 1) rank[e] = (double)count[e];
+        else if (policy == 2) rank[e] = expert_norm[e];
+        else return -1;
+    }
+    return 0;
+}
+
+// The "On demand" baseline (Section 4.1): a portion of the experts is resident
+// and an expert that is asked for and missing is loaded.  The paper gives no
+// replacement rule; reading: least recently used.  One call = one batch.
+//   clock      in/out, incremented once per batch
+//   last_use   in/out [K]: the batch in which each slot's expert was last some
+//              token's own choice (or was loaded)
+// Step 1: every token whose own expert is resident stamps that slot with the
+// new clock; the others add one request to their expert.  Step 2: repeatedly
+// take the most requested missing expert (lowest id among equals) and the slot
+// with the oldest stamp that this batch has not used (lowest slot among
+// equals), pair them, stamp the slot; stop when either runs out.  The maps are
+// NOT changed here (the caller applies the loads); returns the pair count.
+int oracle_on_demand(const int32_t* orig_expert, int T, int E, int K, const int32_t* expert_to_slot,
+                     int64_t* clock, int64_t* last_use, int32_t* changed_slots, int32_t* changed_experts) {
+    *clock += 1;
+    std::vector<int> requests(E, 0);
+    for (int t = 0; t < T; ++t) {
+        int e = orig_expert[t];
+        if (e < 0 || e >= E) return -1;
+        if (expert_to_slot[e] >= 0) last_use[expert_to_slot[e]] = *clock;
+        else requests[e] += 1;
+    }
+    int n = 0;
+    for (;;) {
+        int want = -1;
+        for (int e = 0; e < E; ++e)
+            if (requests[e] > 0 && (want < 0 || requests[e] > requests[want])) want = e;
+        int victim = -1;
+        for (int s = 0; s < K; ++s)
+            if (last_use[s] < *clock && (victim < 0 || last_use[s] < last_use[victim])) victim = s;
+        if (want < 0 || victim < 0) break;
+        changed_slots[n] = victim;
+        changed_experts[n] = want;
+        ++n;
+        requests[want] = 0;
+        last_use[victim] = *clock;
+    }
+    return n;
+}
+
 // Threads the row loops will use (reported next to the oracle's timings).
 int oracle_num_threads(void) {
 #ifdef _OPENMP

@@ -21,6 +21,7 @@ LIB_PATH = os.environ.get("SMOE_LIBRARY") or os.path.join(_HERE, "libswapmoe.so"
 SMOE_OK, SMOE_EINVAL, SMOE_ESTATE, SMOE_EHIP, SMOE_ENOMEM = 0, -1, -2, -3, -4
 SMOE_F32, SMOE_BF16 = 0, 1
 SMOE_GATE_FULL, SMOE_GATE_RENORM = 0, 1
+SMOE_POLICY_IMPORTANCE, SMOE_POLICY_COUNT, SMOE_POLICY_MAGNITUDE = 0, 1, 2
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -58,6 +59,13 @@ _SIGS = {
     "smoe_expert_ffn": (C.c_int, [_vp, _vp, _vp, _i, _vp, _vp]),
     "smoe_combine": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _i, _vp, _vp]),
     "smoe_set_profile_events": (C.c_int, [_vp, _vp, _vp, _vp, _vp]),
+    "smoe_policy_scores": (C.c_int, [_i, _i, _vp, _vp, _vp, _vp]),
+    "smoe_on_demand_plan": (C.c_int, [_vp, _vp, _i, _vp, _vp]),
+    "smoe_profile_memory": (C.c_int, [C.POINTER(smoe_config), _vp]),
+    "smoe_profile_begin": (C.c_int, [_vp, _vp]),
+    "smoe_profile_end": (C.c_int, [_vp, _vp, C.POINTER(C.c_float)]),
+    "smoe_period_inflection": (C.c_int, [_vp, _i, C.c_float]),
+    "smoe_describe_ffn": (C.c_int, [_vp, _i, _i, C.c_char_p, C.c_size_t]),
     "smoe_forward": (C.c_int, [_vp, _vp, _i, _vp, _vp, _i] + [_vp] * 12),
 }
 EXPORTS = tuple(_SIGS)
@@ -193,6 +201,49 @@ def _act_dtype(dtype):
     return torch.float32 if dtype == SMOE_F32 else torch.int16
 
 
+class smoe_memory_profile(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in ("expert_bytes", "resident_bytes", "workspace_bytes", "bank_bytes",
+                                          "router_bytes")]
+
+
+def smoe_policy_scores(policy, E, count, score, expert_norm, rank):
+    _check(_lib.smoe_policy_scores(policy, E, _ptr(count), _ptr(score), _ptr(expert_norm), _ptr(rank)))
+
+
+def smoe_on_demand_plan(layer, orig_expert_host, T, changed_slots, changed_experts) -> int:
+    return _check(_lib.smoe_on_demand_plan(layer, _ptr(orig_expert_host), T, _ptr(changed_slots),
+                                           _ptr(changed_experts)))
+
+
+def smoe_profile_memory(E, K, d_model, d_ff, max_tokens, dtype, gate_mode=SMOE_GATE_FULL, spare_slots=0) -> dict:
+    cfg = smoe_config(E, K, d_model, d_ff, max_tokens, dtype, gate_mode, spare_slots)
+    out = smoe_memory_profile()
+    _check(_lib.smoe_profile_memory(C.byref(cfg), C.byref(out)))
+    return {n: int(getattr(out, n)) for n, _ in smoe_memory_profile._fields_}
+
+
+def smoe_profile_begin(layer, stream=None):
+    _check(_lib.smoe_profile_begin(layer, _stream(stream)))
+
+
+def smoe_profile_end(layer, stream=None) -> float:
+    us = C.c_float(0.0)
+    _check(_lib.smoe_profile_end(layer, _stream(stream), C.byref(us)))
+    return float(us.value)
+
+
+def smoe_period_inflection(latency_us, tolerance) -> int:
+    import numpy as np
+    lat = np.ascontiguousarray(latency_us, np.float32)
+    return _check(_lib.smoe_period_inflection(_ptr(lat), int(lat.shape[0]), C.c_float(tolerance)))
+
+
+def smoe_describe_ffn(layer, T, fused=True) -> str:
+    buf = C.create_string_buffer(256)
+    _check(_lib.smoe_describe_ffn(layer, T, int(fused), buf, 256))
+    return buf.value.decode()
+
+
 def smoe_update_begin(layer, score_host) -> int:
     return _check(_lib.smoe_update_begin(layer, _ptr(score_host)))
 
@@ -284,6 +335,26 @@ class Layer:
         cs = np.empty(self.K, np.int32)
         ce = np.empty(self.K, np.int32)
         n = smoe_select_resident(self.handle, score_host, cs, ce)
+        return [(int(cs[i]), int(ce[i])) for i in range(n)]
+
+    def policy_rank(self, policy):
+        """Host copy of what `policy` ranks the experts by (one read-back of E numbers)."""
+        import numpy as np
+        rank = np.empty(self.E, np.float32)
+        src = {SMOE_POLICY_IMPORTANCE: self.score, SMOE_POLICY_COUNT: self.count,
+               SMOE_POLICY_MAGNITUDE: self.expert_norm}[policy].cpu().numpy()
+        smoe_policy_scores(policy, self.E, src if policy == SMOE_POLICY_COUNT else None,
+                           src if policy == SMOE_POLICY_IMPORTANCE else None,
+                           src if policy == SMOE_POLICY_MAGNITUDE else None, rank)
+        return rank
+
+    def on_demand_plan(self, T):
+        """Load-on-miss plan for the batch just served (reads back its orig_expert)."""
+        import numpy as np
+        oe = self.orig_expert[:T].cpu().numpy()
+        cs = np.empty(self.K, np.int32)
+        ce = np.empty(self.K, np.int32)
+        n = smoe_on_demand_plan(self.handle, oe, T, cs, ce)
         return [(int(cs[i]), int(ce[i])) for i in range(n)]
 
     def update_begin(self, score_host):

@@ -11,6 +11,7 @@
 #include <numeric>
 
 #include "smoe_internal.h"
+#include "swapmoe_profile.h"
 
 namespace {
 thread_local char g_err[512] = "";
@@ -119,6 +120,7 @@ int smoe_destroy(smoe_layer_t* layer) {
     for (auto& st : layer->staged) if (st.done) (void)hipEventDestroy(st.done);
     for (hipEvent_t e : layer->event_pool) (void)hipEventDestroy(e);
     for (hipEvent_t e : layer->released) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : layer->bracket) if (e) (void)hipEventDestroy(e);
     delete layer;
     return SMOE_OK;
 }
@@ -172,6 +174,8 @@ int smoe_bind(smoe_layer_t* L, const float* router_w, void* slot_w1, void* slot_
     for (int i = L->cfg.spare_slots - 1; i >= 0; --i) L->free_stage.push_back(i);
     L->plan.clear();
     L->bank_seen[0] = L->bank_seen[1] = nullptr;
+    L->last_use.assign(L->cfg.K, 0);
+    L->use_clock = 0;
     for (auto& st : L->staged) L->event_pool.push_back(st.done);   // loads of the old binding are forgotten
     L->staged.clear();
     L->slots_set = 0;

@@ -59,6 +59,12 @@ struct smoe_layer {
     bool router_split_done = false;          // made by the first smoe_route after a bind
 
     hipEvent_t prof_ev[4] = {nullptr, nullptr, nullptr, nullptr};   // one-shot FFN profiling events
+    hipEvent_t bracket[2] = {nullptr, nullptr};                     // smoe_profile_begin / _end
+    bool bracket_open = false;
+
+    // load-on-miss baseline: when each slot's expert was last some token's own choice
+    std::vector<int64_t> last_use;
+    int64_t use_clock = 0;
 };
 
 struct smoe_ws_layout {
@@ -102,6 +108,7 @@ int smoe_launch_ffn_f32(const smoe_layer* L, const float* x_perm, const int32_t*
                         float* y_perm, hipStream_t s);
 int smoe_launch_ffn_bf16(const smoe_layer* L, const uint16_t* x_perm, const int32_t* offsets, int T,
                          uint16_t* y_perm, hipStream_t s);
+int smoe_describe_ffn_bf16(const smoe_layer* L, int T, int fused, char* out, size_t n);
 int smoe_launch_combine(const smoe_layer* L, const void* y_perm, const int32_t* inv_perm,
                         const float* gate, const void* residual, int T, void* out, hipStream_t s);
 // packs / copies one expert's two matrices into physical slot `phys`

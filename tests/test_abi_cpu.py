@@ -14,7 +14,8 @@ FAKE = 0x10000          # a non-null, 256-byte aligned "device pointer" that is 
 
 
 def test_exports_match_header():
-    text = open(os.path.join(ROOT, "include", "swapmoe.h")).read()
+    import glob
+    text = "".join(open(h).read() for h in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     declared = set(re.findall(r"\b(smoe_[a-z_]+)\s*\(", text))
     assert declared == set(b.EXPORTS)
@@ -115,9 +116,11 @@ def test_header_is_plain_c():
     gcc = shutil.which("gcc")
     if gcc is None:
         pytest.skip("no C compiler")
-    r = subprocess.run([gcc, "-x", "c", "-std=c99", "-fsyntax-only", "-Wall", "-Werror",
-                        os.path.join(ROOT, "include", "swapmoe.h")], capture_output=True, text=True)
-    assert r.returncode == 0, r.stderr
+    for header in ("swapmoe.h", "swapmoe_profile.h"):
+        r = subprocess.run([gcc, "-x", "c", "-std=c99", "-fsyntax-only", "-Wall", "-Werror", "-I",
+                            os.path.join(ROOT, "include"), os.path.join(ROOT, "include", header)],
+                           capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
 
 
 def test_spare_slots_and_async_calls_without_a_gpu():
@@ -141,3 +144,55 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "ONE GPU" in (r.stderr + r.stdout)
+
+
+def test_policy_unit_on_host():
+    """Rankings and the load-on-miss plan are host code: checked here without a GPU."""
+    count = np.array([5, 0, 9, 9, 1, 2], np.int32)
+    score = np.array([0.5, 0.0, 2.0, 0.1, 3.0, 0.2], np.float32)
+    en = np.array([1.0, 6.0, 2.0, 5.0, 3.0, 4.0], np.float32)
+    rank = np.empty(6, np.float32)
+    for policy, src in ((b.SMOE_POLICY_IMPORTANCE, score), (b.SMOE_POLICY_COUNT, count), (b.SMOE_POLICY_MAGNITUDE, en)):
+        b.smoe_policy_scores(policy, 6, count, score, en, rank)
+        assert np.array_equal(rank, src.astype(np.float32))
+    assert _status(b.smoe_policy_scores, 3, 6, count, score, en, rank) == b.SMOE_EINVAL
+    assert _status(b.smoe_policy_scores, b.SMOE_POLICY_COUNT, 6, None, score, en, rank) == b.SMOE_EINVAL
+    # load on miss on a handle whose slots are all empty: the most requested experts fill slots 0, 1, 2
+    h = b.smoe_create(7, 3, 64, 64, 16, b.SMOE_F32)
+    cs = np.empty(3, np.int32); ce = np.empty(3, np.int32)
+    oe = np.array([3, 4, 5, 6, 6], np.int32)
+    n = b.smoe_on_demand_plan(h, oe, 5, cs, ce)
+    assert n == 3 and cs.tolist() == [0, 1, 2] and ce.tolist() == [6, 3, 4]
+    # the plan changes no map (the caller loads): the same batch again asks for the same loads
+    assert b.smoe_on_demand_plan(h, oe, 5, cs, ce) == 3 and ce.tolist() == [6, 3, 4]
+    assert b.smoe_on_demand_plan(h, oe, 0, cs, ce) == 0          # an empty batch asks for nothing
+    assert _status(b.smoe_on_demand_plan, h, np.array([9], np.int32), 1, cs, ce) == b.SMOE_EINVAL
+    b.smoe_destroy(h)
+
+
+def test_profile_bookkeeping_on_host():
+    """E_memory from the shape alone, and the update-period search on a measured-looking sweep."""
+    m = b.smoe_profile_memory(64, 16, 768, 3072, 32, b.SMOE_BF16, spare_slots=1)
+    per = 2 * 768 * 3072 * 2
+    assert m["expert_bytes"] == per and m["resident_bytes"] == 17 * per and m["bank_bytes"] == 64 * per
+    assert m["router_bytes"] == 64 * 768 * 4
+    h = b.smoe_create(64, 16, 768, 3072, 32, b.SMOE_BF16, spare_slots=1)
+    assert m["workspace_bytes"] == b.smoe_workspace_bytes(h) and b.smoe_slot_weight_bytes(h) * 2 == m["resident_bytes"]
+    b.smoe_destroy(h)
+    with pytest.raises(b.SmoeError):
+        b.smoe_profile_memory(64, 65, 768, 3072, 32, b.SMOE_BF16)
+    # step latency against update frequency, lowest frequency (longest period) first: flat, then it rises
+    periods = [128, 64, 32, 16, 8, 4, 2]
+    lat = [40.7, 41.4, 42.7, 44.4, 48.5, 59.8, 83.3]
+    assert periods[b.smoe_period_inflection(lat, 0.10)] == 16   # 48.5 is the first point above 1.1 x 40.7
+    assert periods[b.smoe_period_inflection(lat, 0.03)] == 64   # 42.7 > 1.03 x 40.7
+    assert periods[b.smoe_period_inflection(lat, 2.0)] == 2     # never rises that much: the whole sweep is flat
+    assert b.smoe_period_inflection([50.0, 45.0, 44.0, 49.0], 0.10) == 2   # the floor follows the minimum so far
+    assert b.smoe_period_inflection([7.0], 0.1) == 0
+    with pytest.raises(b.SmoeError):
+        b.smoe_period_inflection([], 0.1)
+    # the event bracket refuses an end without a begin, before any HIP call
+    h = b.smoe_create(8, 2, 64, 256, 128, b.SMOE_F32)
+    us = C.c_float()
+    assert b._lib.smoe_profile_end(h, None, C.byref(us)) == b.SMOE_ESTATE
+    b.smoe_destroy(h)

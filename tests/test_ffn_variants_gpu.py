@@ -19,14 +19,17 @@ from harness import Case, max_abs_rel, to_dev, to_host, values
 
 pytestmark = pytest.mark.gpu
 
-# indices of launch_variant in csrc/ffn_bf16.hip: (first product, second product)
-PAIRS = [(1, 1), (3, 3), (4, 4), (5, 5), (6, 6), (8, 8), (10, 10), (10, 1), (8, 3), (5, 6), (1, 10)]
+# indices of launch_variant in csrc/ffn_bf16.hip: (first product, second product); the 256-row tile
+# (10) exists for the first product only
+PAIRS = [(1, 1), (3, 3), (4, 4), (5, 5), (6, 6), (8, 8), (10, 1), (10, 8), (8, 3), (5, 6), (4, 6)]
 
 
 @pytest.mark.parametrize("v1,v2", PAIRS)
-@pytest.mark.parametrize("d_ff", [256, 160])       # 160: reduction length of the second product not a multiple of 64
-def test_tile_variant(v1, v2, d_ff):
-    cfg = wl.MoEConfig("variants", E=8, K=3, d_model=128, d_ff=d_ff, T=1000, dtype=wl.BF16, seed=31)
+# (d_model, d_ff): 160 makes the second product's reduction length no multiple of 64; 768 x 768 is the
+# Switch-base reduction length (12 slices of 64) in both products
+@pytest.mark.parametrize("d_model,d_ff", [(128, 256), (128, 160), (768, 768)])
+def test_tile_variant(v1, v2, d_model, d_ff):
+    cfg = wl.MoEConfig("variants", E=8, K=3, d_model=d_model, d_ff=d_ff, T=1000, dtype=wl.BF16, seed=31)
     os.environ["SMOE_FFN_VARIANT"] = f"{v1},{v2}"
     try:
         c = Case(cfg, resident=[5, 0, 6], router_scale=20.0)

@@ -466,3 +466,58 @@ def test_update_brings_in_the_preferred_expert():
     full = oracle.layer_forward(x, Wr, W1, W2, e2s_full, out_dtype=oracle.F64)
     assert np.array_equal(r2["out"], full["out"])
     assert not np.array_equal(r["out"], full["out"])
+
+
+# --------------------------------------------------------------------- policies
+def test_policy_rankings_and_update_rule_by_hand():
+    """The three rankings the evaluation compares feed the same update rule: Eq. 1 score
+    (SwapMoE), token count ("simple scheduling", Section 4.5) and expert magnitude (the
+    "Pruning" baseline, Section 4.1).  Expected resident sets written out by hand."""
+    count = np.array([5, 0, 9, 9, 1, 2], np.int32)
+    score = np.array([0.5, 0.0, 2.0, 0.1, 3.0, 0.2])
+    en = np.array([1.0, 6.0, 2.0, 5.0, 3.0, 4.0])
+    s2e = np.array([0, 1, 2], np.int32)
+    e2s = np.array([0, 1, 2, -1, -1, -1], np.int32)
+    want = {
+        oracle.POLICY_IMPORTANCE: (score, [0, 4, 2], [(1, 4)]),             # top 3 by score: 4, 2, 0
+        oracle.POLICY_COUNT: (count.astype(np.float64), [0, 3, 2], [(1, 3)]),   # 2 and 3 tie at 9, then 0
+        oracle.POLICY_MAGNITUDE: (en, [3, 1, 5], [(0, 3), (2, 5)]),          # 1, 3, 5; newcomers by magnitude
+    }
+    for policy, (rank_want, s2e_want, loads_want) in want.items():
+        rank = oracle.policy_scores(policy, count, score, en)
+        assert np.array_equal(rank, rank_want)
+        n_s2e, n_e2s, loads = oracle.select_resident(rank, s2e, e2s)
+        assert n_s2e.tolist() == s2e_want and loads == loads_want, policy
+        assert np.array_equal(n_e2s[n_s2e], np.arange(3))
+    with pytest.raises(ValueError):
+        oracle.policy_scores(7, count, score, en)
+
+
+def test_on_demand_least_recently_used_by_hand():
+    """Load-on-miss with least-recently-used replacement over four batches, every plan worked
+    out by hand (K = 2 slots, E = 5 experts, slots start with experts 0 and 1)."""
+    K, E = 2, 5
+    s2e = np.array([0, 1], np.int32)
+    e2s = np.array([0, 1, -1, -1, -1], np.int32)
+    od = oracle.OnDemand(K)
+    script = [
+        # batch's original choices, expected loads, why
+        ([0, 2, 2, 3], [(1, 2)]),          # slot 0 is used now; 2 (asked twice) beats 3; only slot 1 is free to evict
+        ([1, 1, 4],    [(0, 1), (1, 4)]),  # no hit; both slots equally stale -> lower slot first; 1 (twice) before 4
+        ([1, 0, 0, 2], [(1, 0)]),          # expert 1 (slot 0) is hit; 0 (twice) replaces the stale slot 1; 2 finds no slot
+        ([3],          [(0, 3)]),          # both stamped in batch 3: the lower slot goes
+        ([],           []),                # an empty batch asks for nothing
+    ]
+    for choices, loads_want in script:
+        loads = od.plan(np.array(choices, np.int32), e2s)
+        assert loads == loads_want, (choices, loads)
+        for sl, ex in loads:
+            e2s[s2e[sl]] = -1
+            s2e[sl] = ex
+            e2s[ex] = sl
+    assert s2e.tolist() == [3, 0] and int(od.clock[0]) == 5
+    # a resident expert is never loaded, and no slot is evicted twice in one batch
+    od2 = oracle.OnDemand(3)
+    e2s3 = np.array([0, 1, 2, -1, -1, -1, -1], np.int32)
+    loads = od2.plan(np.array([3, 4, 5, 6, 6], np.int32), e2s3)
+    assert loads == [(0, 6), (1, 3), (2, 4)]

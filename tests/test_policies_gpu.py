@@ -1,0 +1,140 @@
+"""Scheduling policies over the same kernels (Section 4.1 baselines and the
+Section 4.5 ablation), and the measurable part of the offline profile
+(Section 3.3-3.4.1, Appendix A.1).
+
+A decode-shaped stream (Switch-base-64 decode shape: T = 32, E = 64, K = 16)
+runs free on the library under each policy; the oracle is given the same
+inputs, keeps its own accumulators and use stamps, and applies its own ranking
+and update rule.  Step by step: the loads each side plans, the resident sets,
+and the number of tokens that found their own expert resident must agree.
+(The accuracy side of the paper's comparison needs its datasets and is out of
+scope; what is compared here is the bookkeeping that decides what is resident.)
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2308_15030_amd import binding as b
+from paper_2308_15030_amd import workloads as wl
+from harness import Case, max_abs_rel, to_dev, to_host, values
+
+pytestmark = pytest.mark.gpu
+
+STEPS = 48
+POLICIES = {"importance": (b.SMOE_POLICY_IMPORTANCE, oracle.POLICY_IMPORTANCE),
+            "count": (b.SMOE_POLICY_COUNT, oracle.POLICY_COUNT),
+            "magnitude": (b.SMOE_POLICY_MAGNITUDE, oracle.POLICY_MAGNITUDE)}
+
+
+def _follow(c, s2e, e2s, loads):
+    for sl, ex in loads:
+        c.load(sl, ex)
+        e2s[s2e[sl]] = -1
+        s2e[sl] = ex
+        e2s[ex] = sl
+
+
+@pytest.mark.parametrize("policy", ["importance", "count", "magnitude", "on_demand"])
+def test_policy_follows_the_oracle(policy):
+    cfg = wl.CONFIGS["c4"]
+    c = Case(cfg, bank_experts=range(cfg.E), x=np.zeros((cfg.T, cfg.d_model), np.uint16))
+    L, T, K = c.L, cfg.T, cfg.K
+    xs = wl.decode_stream(cfg, STEPS)
+    d_xs = to_dev(xs.reshape(STEPS * T, cfg.d_model)).view(STEPS, T, cfg.d_model)
+    s2e, e2s = c.s2e.copy(), c.e2s.copy()                   # the oracle's own maps
+    od = oracle.OnDemand(K)
+    if policy == "magnitude":                                # static: the K largest experts, chosen once
+        rank = L.policy_rank(b.SMOE_POLICY_MAGNITUDE)
+        np.testing.assert_allclose(rank, c.en_oracle, rtol=1e-5)
+        loads = L.select_resident(rank)
+        _, _, ref_loads = oracle.select_resident(oracle.policy_scores(oracle.POLICY_MAGNITUDE, np.zeros(cfg.E, np.int32),
+                                                                      np.zeros(cfg.E), c.en_oracle), s2e, e2s)
+        assert loads == ref_loads and len(loads) > 0
+        _follow(c, s2e, e2s, loads)
+    state, lib_hits, ref_hits, swaps = None, 0, 0, 0
+    for step in range(STEPS):
+        first = step % cfg.period == 0
+        l_s2e, l_e2s = L.maps()
+        assert np.array_equal(l_s2e, s2e) and np.array_equal(l_e2s, e2s), step      # resident sets agree
+        out = L.forward_fused(d_xs[step], T, accumulate=0 if first else 1)
+        torch.cuda.synchronize()
+        idx = [c.bank_pos[int(e)] for e in s2e]
+        ref = oracle.layer_forward(xs[step], c.Wr, c.W1_bank[idx], c.W2_bank[idx], e2s)
+        ok = ~ref["ambiguous"]
+        g_oe = to_host(L.orig_expert)
+        assert np.array_equal(g_oe[ok], ref["orig_expert"][ok]), step
+        assert np.array_equal(to_host(L.slot)[ok], ref["slot"][ok]), step
+        assert max_abs_rel(values(to_host(out), cfg.dtype)[ok], values(ref["out"], cfg.dtype)[ok]) <= 2e-2
+        # hits: tokens served by their own expert (near-tie tokens counted with the library's choice on both sides)
+        lib_hits += int((l_e2s[g_oe] >= 0).sum())
+        ref_hits += int((e2s[np.where(ok, ref["orig_expert"], g_oe)] >= 0).sum())
+        state = oracle.importance(g_oe, ref["orig_gate"], ref["xnorm"], c.en_oracle, state=None if first else state)
+        if policy == "on_demand":                            # after every batch
+            loads = L.on_demand_plan(T)
+            ref_loads = od.plan(g_oe, e2s)
+            assert loads == ref_loads, (step, loads, ref_loads)
+            swaps += len(loads)
+            _follow(c, s2e, e2s, loads)
+        elif policy != "magnitude" and (step + 1) % cfg.period == 0:
+            lp, op = POLICIES[policy]
+            rank = L.policy_rank(lp)
+            ref_rank = oracle.policy_scores(op, state[0], state[2], c.en_oracle)
+            np.testing.assert_allclose(rank, ref_rank, rtol=1e-4, atol=1e-30)
+            loads = L.select_resident(rank)
+            _, _, ref_loads = oracle.select_resident(ref_rank, s2e, e2s)
+            if loads != ref_loads:                           # only a near-tie at the K-th place may differ
+                order = np.sort(ref_rank)[::-1]
+                assert (order[K - 1] - order[K]) / max(order[K - 1], 1e-30) < 1e-4, (step, loads, ref_loads)
+            swaps += len(loads)
+            _follow(c, s2e, e2s, loads)                      # the oracle follows the library's choice
+    assert lib_hits == ref_hits
+    if policy != "magnitude":
+        assert swaps > 0, "the stream never changed the resident set: the test exercises nothing"
+    print(f"policy {policy}: hit rate {lib_hits / (STEPS * T):.3f}, {swaps} experts loaded in {STEPS} steps", flush=True)
+    L.close()
+
+
+def test_profile_and_period_sweep():
+    """The offline profile as far as the layer itself provides it: bytes per expert from the
+    shape, measured layer latency and expert loading time through the event bracket, and the
+    update-period search on a short measured sweep (a smoke test: the numbers only have to be
+    sane, the inflection rule itself is pinned on the CPU)."""
+    cfg = wl.CONFIGS["c4"]
+    c = Case(cfg, bank_experts=range(cfg.E), x=np.zeros((cfg.T, cfg.d_model), np.uint16))
+    L, T = c.L, cfg.T
+    m = b.smoe_profile_memory(cfg.E, cfg.K, cfg.d_model, cfg.d_ff, T, cfg.dtype)
+    assert m["expert_bytes"] == 2 * cfg.d_model * cfg.d_ff * 2
+    assert L.slot_w1.numel() + L.slot_w2.numel() == m["resident_bytes"] and L.workspace.numel() == m["workspace_bytes"]
+    xs = wl.decode_stream(cfg, 64)
+    d_xs = to_dev(xs.reshape(64 * T, cfg.d_model)).view(64, T, cfg.d_model)
+    for i in range(4):
+        L.forward_fused(d_xs[i], T, accumulate=1)
+    reps = 32
+    b.smoe_profile_begin(L.handle)
+    for i in range(reps):
+        L.forward_fused(d_xs[i], T, accumulate=1)
+    layer_us = b.smoe_profile_end(L.handle) / reps           # E_latency of the layer at this K
+    b.smoe_profile_begin(L.handle)
+    for i in range(8):
+        c.load(i % cfg.K, int(c.s2e[i % cfg.K]))             # refresh: the cost of loading one expert
+    load_us = b.smoe_profile_end(L.handle) / 8
+    assert 5.0 < layer_us < 500.0 and 1.0 < load_us < 500.0
+    with pytest.raises(b.SmoeError):
+        b.smoe_profile_end(L.handle)                         # no begin before it
+    # period sweep, lowest update frequency first
+    periods, lat = [32, 8, 2, 1], []
+    for p in periods:
+        b.smoe_profile_begin(L.handle)
+        for i in range(64):
+            L.forward_fused(d_xs[i], T, accumulate=0 if i % p == 0 else 1)
+            if (i + 1) % p == 0:
+                for sl, ex in L.select_resident(L.policy_rank(b.SMOE_POLICY_IMPORTANCE)):
+                    c.load(sl, ex)
+        lat.append(b.smoe_profile_end(L.handle) / 64)
+    k = b.smoe_period_inflection(lat, 0.25)
+    assert 0 <= k < len(periods)
+    assert lat[-1] > lat[0], "updating after every step must cost more than updating every 32"
+    print(f"profile: layer {layer_us:.1f} us, expert load {load_us:.1f} us, sweep {dict(zip(periods, np.round(lat, 1)))} "
+          f"-> period {periods[k]}", flush=True)
+    L.close()
