@@ -31,40 +31,49 @@ __global__ void set_map_kernel(int32_t* e2s, int32_t* s2e, int32_t* phys, int sl
     }
 }
 
-// One thread builds one 16-byte packed unit: 8 consecutive reduction rows of
-// one feature column.  Within a wave the 32 feature columns are adjacent, so
-// each of the 8 row reads is a 64-byte run and the write is a full 1-KiB block.
-__device__ __forceinline__ void pack_unit(const uint16_t* __restrict__ src, int R, int N,
-                                          uint4* __restrict__ dst, size_t unit) {
-    size_t total = (size_t)(N / 32) * (R / 16) * 64;
-    if (unit >= total) return;
-    int lane = (int)(unit & 63);
-    size_t blk = unit >> 6;
-    int rb = (int)(blk % (R / 16)), nb = (int)(blk / (R / 16));
-    int n = nb * 32 + (lane & 31);
-    int r0 = rb * 16 + (lane >> 5) * 8;
-    uint32_t w[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        uint32_t lo = src[(size_t)(r0 + 2 * i) * N + n];
-        uint32_t hi = src[(size_t)(r0 + 2 * i + 1) * N + n];
-        w[i] = lo | (hi << 16);
+// One workgroup re-lays a tile of 16 reduction rows x 128 feature columns (4 blocks of the
+// packed order).  The source rows are read with 16-byte pieces, 256 contiguous bytes per
+// row, and turned through LDS; each thread then gathers one packed unit (8 consecutive
+// reduction rows of one feature column) and the workgroup writes four full 1-KiB blocks.
+constexpr int PACK_COLS = 128;
+constexpr int PACK_LD = PACK_COLS + 8;       // LDS row pitch in elements (16-byte aligned rows)
+
+__device__ __forceinline__ void pack_tile(const uint16_t* __restrict__ src, int R, int N,
+                                          uint4* __restrict__ dst, int tile, uint16_t* lds) {
+    const int ctiles = (N + PACK_COLS - 1) / PACK_COLS;
+    const int rb = tile / ctiles, ct = tile - rb * ctiles;       // 16-row block, 128-column tile
+    const int n0 = ct * PACK_COLS, r0 = rb * 16, tid = threadIdx.x;
+    {   // thread t brings 8 columns of row t / 16
+        const int row = tid >> 4, col = n0 + (tid & 15) * 8;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (col < N) v = *(const uint4*)(src + (size_t)(r0 + row) * N + col);   // N is a multiple of 32: whole pieces
+        *(uint4*)&lds[row * PACK_LD + (tid & 15) * 8] = v;
     }
-    dst[unit] = make_uint4(w[0], w[1], w[2], w[3]);
+    __syncthreads();
+    const int nbl = tid >> 6, lane = tid & 63;                    // feature block inside the tile, lane of the unit
+    const int nb = ct * (PACK_COLS / 32) + nbl;
+    if (nb * 32 < N) {
+        const int c = nbl * 32 + (lane & 31), rr = (lane >> 5) * 8;
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            w[i] = (uint32_t)lds[(rr + 2 * i) * PACK_LD + c] | ((uint32_t)lds[(rr + 2 * i + 1) * PACK_LD + c] << 16);
+        dst[((size_t)nb * (R / 16) + rb) * 64 + lane] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
 }
 
-// Loads one expert into a physical slot in a single launch: blocks [0, nblk)
-// pack W1 [d_model, d_ff], blocks [nblk, 2 nblk) pack W2 [d_ff, d_model] (both
-// have d_model * d_ff / 8 units); with map_slot >= 0 the first thread also
-// switches the maps.  The maps are read only by later launches of the stream, which
+// Loads one expert into a physical slot in a single launch: blocks [0, nblk1) re-lay
+// W1 [d_model, d_ff], the rest W2 [d_ff, d_model]; with map_slot >= 0 the first thread
+// also switches the maps.  The maps are read only by later launches of the stream, which
 // start after this whole launch (weights included) has completed.
 __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint16_t* __restrict__ w1, const uint16_t* __restrict__ w2,
                                                         int d_model, int d_ff, uint4* __restrict__ dst1,
-                                                        uint4* __restrict__ dst2, int nblk, int32_t* e2s,
+                                                        uint4* __restrict__ dst2, int nblk1, int32_t* e2s,
                                                         int32_t* s2e, int32_t* phys, int map_slot, int expert,
                                                         int old_expert, int p) {
-    if ((int)blockIdx.x < nblk) pack_unit(w1, d_model, d_ff, dst1, (size_t)blockIdx.x * 256 + threadIdx.x);
-    else pack_unit(w2, d_ff, d_model, dst2, (size_t)(blockIdx.x - nblk) * 256 + threadIdx.x);
+    __shared__ __align__(16) uint16_t lds[16 * PACK_LD];
+    if ((int)blockIdx.x < nblk1) pack_tile(w1, d_model, d_ff, dst1, blockIdx.x, lds);
+    else pack_tile(w2, d_ff, d_model, dst2, blockIdx.x - nblk1, lds);
     if (map_slot >= 0 && blockIdx.x == 0 && threadIdx.x == 0) {
         if (old_expert >= 0) e2s[old_expert] = -1;
         e2s[expert] = map_slot;
@@ -141,12 +150,12 @@ int smoe_launch_pack_slot(const smoe_layer* L, int slot, const void* w1_src, con
     const size_t per = (size_t)c.d_model * c.d_ff;               // elements per matrix
     if (map_done) *map_done = 0;
     if (c.dtype == SMOE_BF16) {
-        size_t units = per / 8;
-        const int nblk = (int)((units + 255) / 256);
+        const int nblk1 = (c.d_model / 16) * ((c.d_ff + PACK_COLS - 1) / PACK_COLS);
+        const int nblk2 = (c.d_ff / 16) * ((c.d_model + PACK_COLS - 1) / PACK_COLS);
         uint4* d1 = (uint4*)((uint16_t*)L->slot_w1 + (size_t)slot * per);
         uint4* d2 = (uint4*)((uint16_t*)L->slot_w2 + (size_t)slot * per);
-        hipLaunchKernelGGL(pack_bf16_kernel, dim3(2 * nblk), dim3(256), 0, s, (const uint16_t*)w1_src,
-                           (const uint16_t*)w2_src, c.d_model, c.d_ff, d1, d2, nblk, L->d_expert_to_slot,
+        hipLaunchKernelGGL(pack_bf16_kernel, dim3(nblk1 + nblk2), dim3(256), 0, s, (const uint16_t*)w1_src,
+                           (const uint16_t*)w2_src, c.d_model, c.d_ff, d1, d2, nblk1, L->d_expert_to_slot,
                            L->d_slot_to_expert, L->d_phys, map_slot, expert, old_expert, slot);
         if (map_done && map_slot >= 0) *map_done = 1;
     } else {

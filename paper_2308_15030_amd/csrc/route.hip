@@ -6,7 +6,8 @@
 // Figure 4(b)).  |x|_2 is produced on the way because x is already in flight
 // (it is the first factor of the importance score, Eq. 1).
 //
-// One workgroup of 256 threads owns 32 tokens and all E experts.  x and Wr are
+// fp32 activations (route_kernel; the bf16 kernel has its own description below):
+// one workgroup of 256 threads owns 32 tokens and all E experts.  x and Wr are
 // staged through LDS in slices of 64 along d_model; thread (ty, tx) keeps a
 // 2-token x (E/16)-expert block of logits in registers.  Every logit is one
 // sequential fp32 FMA chain in ascending j, so results do not depend on the
@@ -180,10 +181,13 @@ __global__ __launch_bounds__(THREADS) void route_kernel(
 // weights are kept in MFMA operand order in the workspace (made on the first
 // smoe_route after smoe_bind).
 //
-// One workgroup = 32 tokens x all experts.  Its 4 waves split the reduction
-// (d_model) four ways, each accumulating a partial [experts x 32 tokens] tile;
-// the partials meet in LDS and are added in wave order (fixed, so results are
-// reproducible), then the same 8-lanes-per-token epilogue as above runs.
+// One workgroup = one or two blocks of 32 tokens x all experts.  Its NWR waves
+// (8 up to 64 experts, 4 above) split the reduction (d_model) NWR ways, each
+// accumulating a partial [experts x tokens] tile; the partials meet in LDS and
+// are added in wave order (fixed, so results are reproducible).  In the
+// epilogue every thread takes part: lane l of wave w owns token l % 32 and
+// every (2 NWR)-th expert, and the per-token arg-max, masked arg-max and softmax
+// sums meet through small LDS tables, again in wave order.
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -439,7 +443,6 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
     if (TB > 1) __syncthreads();                      // the tables are reused by the next block
     }
     if (TB > 1 || !tail.perm) return;
-    const int t0 = tw0;
     // ---- single-workgroup tail (T <= RT, one workgroup): ranking and importance
     __shared__ int32_t s_cnt[256], s_off[256];
     for (int k = tid; k < 256; k += THREADS) s_cnt[k] = 0;
