@@ -439,6 +439,12 @@ def main():
                     "us_gemm2": round(g2.mean() * 1e6, 2), "launches_timed": 2 * len(ev_used),
                     "mean_active_slots": round(act, 2),
                     "hbm_bytes_per_launch_algorithmic": bytes_launch}
+            if kernels_now.startswith("decode_first_kernel"):
+                # the first launch does not wait for the routing: it streams the first matrix of all K slots
+                streamed = 2.0 * cfg.K * cfg.d_model * cfg.d_ff
+                roof.update(first_launch_streams_all_slots=True, first_launch_bytes_streamed=streamed,
+                            first_launch_streamed_GBs=round(streamed / g1.mean() / 1e9, 1),
+                            second_launch_GBs=round(bytes_launch / g2.mean() / 1e9, 1))
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -465,7 +471,7 @@ def main():
 
     config = {"workload": cfg.name, "E": cfg.E, "K": cfg.K, "d_model": cfg.d_model, "d_ff": cfg.d_ff,
               "tokens": T, "layers": L,
-              "entry": "five separate calls" if args.separate_calls else "smoe_forward (fused, 4 launches; 3 when tokens <= 32)",
+              "entry": "five separate calls" if args.separate_calls else "smoe_forward (one call: 4 launches for prefill, 2 for a decode-sized batch)",
               "step": "route+importance+permute+expert_ffn+combine over all layers"}
     if decode:
         config.update(update_period=cfg.period, experts_swapped=swaps, updates=args.updates, bank=args.bank,

@@ -229,10 +229,14 @@ int smoe_expert_ffn(smoe_layer_t* layer, const void* x_perm, const int32_t* offs
  * reduces the importance sums, the first FFN product reads its rows from x
  * through perm (x_perm is never written) and the second writes
  * gate * y (+ residual) straight to out in token order (y_perm is never
- * written).  With at most 32 tokens the router's single workgroup does the
- * ranking and the importance sums as well: three launches.  All the per-token
- * and per-expert outputs of the individual calls
- * are produced: orig_expert, orig_gate, slot, gate, xnorm [T]; count, gsum,
+ * written).  A decode-sized batch (at most 32 tokens, a few per slot, at most
+ * 64 experts) takes two launches: the router, which then also ranks the tokens
+ * and adds the importance sums, runs as one workgroup of the launch whose other
+ * workgroups compute the first product for every slot and every token of the
+ * batch (it does not wait for the routing; the weights of slots that turn out
+ * empty are streamed for nothing), and the second product picks each token's
+ * row from its slot.  All the per-token and per-expert outputs of the individual
+ * calls are produced: orig_expert, orig_gate, slot, gate, xnorm [T]; count, gsum,
  * score [E] (accumulate as in smoe_importance); perm, inv_perm [T];
  * offsets [K+1].  residual may be NULL and may alias x; out must not alias x.
  * T = 0 leaves what the separate calls leave: offsets = 0 and, with

@@ -544,6 +544,15 @@ int smoe_forward(smoe_layer_t* L, const void* x, int T, const void* residual, vo
         if (rc) return rc;
         L->router_split_done = true;
     }
+    if (smoe_decode_first_applies(L, T) && smoe_ffn_dense_path(L, T)) {
+        // decode step in two launches: the router (with its ranking tail) next to the first product
+        // of every slot, then the second product of the slots that got tokens
+        rc = smoe_launch_decode_first(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, count, gsum, score, accumulate,
+                                      perm, inv_perm, offsets, s, L->prof_ev[0], L->prof_ev[1]);
+        if (!rc) rc = smoe_launch_ffn_bf16_dense_second(L, slot, gate, (const uint16_t*)residual, T, (uint16_t*)out, s);
+        L->prof_ev[0] = L->prof_ev[1] = L->prof_ev[2] = L->prof_ev[3] = nullptr;
+        return rc;
+    }
     if (T <= 32) {   // decode-sized batch: the router's one workgroup ranks and accumulates as well
         rc = smoe_launch_route_rank_small(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, count, gsum, score,
                                           accumulate, perm, inv_perm, offsets, s);

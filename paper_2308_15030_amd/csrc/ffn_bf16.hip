@@ -969,7 +969,9 @@ int smoe_describe_ffn_bf16(const smoe_layer* L, int T, int fused, char* out, siz
         const int R = first ? L->cfg.d_model : L->cfg.d_ff;
         const char* shape = nullptr;                       // AF, MAXB, NW, BKT, PD, OCC of launch_variant
         std::string name;
-        if (fused && T <= 32 && v[0] == 5 && v[1] == 6) name = first ? "dense_gemm_bf16<6, 1, true>" : "dense_gemm_bf16<4, 4, false>";
+        if (fused && T <= 32 && v[0] == 5 && v[1] == 6 && smoe_decode_first_applies(L, T))
+            name = first ? (L->cfg.E <= 32 ? "decode_first_kernel<1>" : "decode_first_kernel<2>") : "dense_gemm_bf16<4, 4, false>";
+        else if (fused && T <= 32 && v[0] == 5 && v[1] == 6) name = first ? "dense_gemm_bf16<6, 1, true>" : "dense_gemm_bf16<4, 4, false>";
         else if (v[i] == 5) name = std::string("small_gemm_bf16<4, 1, ") + (first ? "true>" : "false>");
         else if (v[i] == 6) name = std::string("small_gemm_bf16<4, 4, ") + (first ? "true>" : "false>");
         else if (R % 64 != 0) shape = "1, 4, 4, 32, ";
@@ -1003,6 +1005,24 @@ int smoe_launch_ffn_bf16(const smoe_layer* L, const uint16_t* x_perm, const int3
     launch_variant<true>(v1, x_perm, L->slot_w1, offsets, c.K, h, c.d_model, c.d_ff, T, none, s, L->prof_ev[0], L->prof_ev[1]);
     launch_variant<false>(v2, h, L->slot_w2, offsets, c.K, y_perm, c.d_ff, c.d_model, T, none, s, L->prof_ev[2], L->prof_ev[3]);
     return smoe_check_hip(hipGetLastError(), "smoe_expert_ffn launch");
+}
+
+bool smoe_ffn_dense_path(const smoe_layer* L, int T) {
+    int v1, v2;
+    pick_variants(L, T, v1, v2);
+    return T <= 32 && v1 == 5 && v2 == 6;
+}
+
+// Second product of a decode-sized batch whose first product was computed for every slot (the
+// fused decode launch): reads h[slot][feature / 8][token], keeps the routed tokens' columns.
+int smoe_launch_ffn_bf16_dense_second(const smoe_layer* L, const int32_t* slot_of, const float* gate,
+                                      const uint16_t* residual, int T, uint16_t* out, hipStream_t s) {
+    const smoe_config& c = L->cfg;
+    const int32_t* phys = c.spare_slots > 0 ? L->d_phys : nullptr;
+    smoe_launch_timed(dense_gemm_bf16<4, 4, false>, dim3(c.K * (c.d_model >> 5)), dim3(256), s, L->prof_ev[2], L->prof_ev[3],
+                      (const uint16_t*)L->d_hidden, (const uint4*)L->slot_w2, slot_of, T, out, c.d_ff, c.d_model, phys, gate,
+                      residual);
+    return smoe_check_hip(hipGetLastError(), "smoe_forward: FFN launch");
 }
 
 // Fused form used by smoe_forward: the first product gathers its rows from x

@@ -245,8 +245,8 @@ struct TailArgs {
 // when the batch has more 32-token blocks than the chip has compute units a workgroup takes
 // two blocks and the weights are fetched half as often.
 template <int NEB, int NWR, int TB>
-__global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
-    const uint16_t* __restrict__ x, const uint4* __restrict__ Wsplit, const int32_t* __restrict__ e2s,
+__device__ __forceinline__ void route_mfma_body(
+    const int block, const uint16_t* __restrict__ x, const uint4* __restrict__ Wsplit, const int32_t* __restrict__ e2s,
     int T, int d, int E, int gate_mode,
     int32_t* __restrict__ orig_expert, float* __restrict__ orig_gate, int32_t* __restrict__ slot,
     float* __restrict__ gate, float* __restrict__ xnorm, int32_t* __restrict__ hist32, int K,
@@ -268,7 +268,7 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
     // wave index as a scalar: loop bounds that guard MFMAs must be wave-uniform for the
     // compiler as well (an MFMA under a lane mask still runs for every lane)
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-    const int tw0 = blockIdx.x * RT * TB;         // first token of the workgroup
+    const int tw0 = block * RT * TB;              // first token of the workgroup
     for (int e = tid; e < EP; e += THREADS) s_e2s[e] = e < E ? e2s[e] : -1;
 
     const int nkb = d >> 4;
@@ -437,7 +437,7 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
         for (int k = tid; k < K; k += THREADS) {
             int c = 0;
             for (int i = 0; i < n; ++i) c += s_slot[i] == k;
-            hist32[((size_t)blockIdx.x * TB + tb) * K + k] = c;
+            hist32[((size_t)block * TB + tb) * K + k] = c;
         }
     }
     if (TB > 1) __syncthreads();                      // the tables are reused by the next block
@@ -511,6 +511,110 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
         tail.gsum[e] = tail.accumulate ? g0 + g[0] : g[0];
         tail.score[e] = tail.accumulate ? r0 + sc : sc;
     }
+}
+
+template <int NEB, int NWR, int TB>
+__global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
+    const uint16_t* __restrict__ x, const uint4* __restrict__ Wsplit, const int32_t* __restrict__ e2s,
+    int T, int d, int E, int gate_mode,
+    int32_t* __restrict__ orig_expert, float* __restrict__ orig_gate, int32_t* __restrict__ slot,
+    float* __restrict__ gate, float* __restrict__ xnorm, int32_t* __restrict__ hist32, int K,
+    const TailArgs tail) {
+    route_mfma_body<NEB, NWR, TB>(blockIdx.x, x, Wsplit, e2s, T, d, E, gate_mode, orig_expert, orig_gate, slot, gate, xnorm,
+                                  hist32, K, tail);
+}
+
+// ---------------------------------------------------------------------------
+// Decode step, first launch (bf16, at most 32 tokens, at most 64 experts): the router and the
+// first FFN product side by side.  The router of a 32-token batch is one workgroup that needs
+// ~9 us for 340 KB of operands, a softmax epilogue and the ranking tail, while the other 255
+// compute units wait for its slot ids only to learn which slots are empty.  Here the last
+// workgroup of the launch is that router, and the others compute the first product for EVERY
+// slot and EVERY token of the batch at once: workgroup (slot, feature tile) multiplies all T
+// tokens, staged once in LDS, by the slot's weight tile and stores the hidden activations
+// h[slot][feature / 8][token] for all of them.  An MFMA column depends on its own token only
+// and the reduction runs in the same order as in the other FFN kernels, so the columns that
+// the second product later picks (the tokens routed to the slot) hold the same bits as on the
+// sorted path.  The price is the weight matrices of the slots nobody was routed to (3 of 16 on
+// the decode workload, +24 % bytes for this launch); what it buys is the router's whole time.
+// 8 waves per workgroup, one 32-feature block per wave; the token operands come from LDS
+// (row pitch d_model + 8 elements: conflict-free 16-byte reads), so the vector-memory pipe
+// carries nothing but the 1-KiB weight loads, 16 of them in flight per wave.
+__device__ __forceinline__ void dense_first_all(const uint16_t* __restrict__ x, const uint4* __restrict__ Wp,
+                                                int T, uint16_t* __restrict__ h, int R, int N,
+                                                const int32_t* __restrict__ phys, int block) {
+    extern __shared__ __align__(16) float smem[];
+    uint16_t* xs = (uint16_t*)smem;                        // [32][R + 8]
+    constexpr int G = 8, NWV = 8;
+    const int nfb = N >> 5, nrb = R >> 4, ldx = R + 8;
+    const int ftiles = (nfb + NWV - 1) / NWV;
+    const int slot = block / ftiles, ftile = block - slot * ftiles;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int fb = ftile * NWV + wave;
+    const bool fb_ok = fb < nfb;
+    const uint4* wp = Wp + ((size_t)(phys ? phys[slot] : slot) * nfb + min(fb, nfb - 1)) * nrb * 64 + lane;
+    uint4 wA[G], wB[G];
+    auto fetch_w = [&](uint4 (&w)[G], int g0) {
+#pragma unroll
+        for (int i = 0; i < G; ++i) w[i] = wp[(size_t)min(g0 + i, nrb - 1) * 64];      // past the end: reloaded, not used
+    };
+    fetch_w(wA, 0);                                        // on their way while the tokens are staged
+    const int cpr = R >> 3;                                // 16-byte pieces per token row
+    for (int idx = tid; idx < 32 * cpr; idx += NWV * 64) {
+        const int r = idx / cpr, c = idx - r * cpr;
+        uint4 v = make_uint4(0, 0, 0, 0);                  // rows past the batch are zero
+        if (r < T) v = *(const uint4*)(x + (size_t)r * R + c * 8);
+        *(uint4*)&xs[r * ldx + c * 8] = v;
+    }
+    __syncthreads();
+    const uint16_t* xrow = xs + (lane & 31) * ldx + (lane >> 5) * 8;
+    f32x16 acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    auto consume = [&](uint4 (&w)[G], int g0) {
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            // steps past the end of the reduction multiply by a zero token operand
+            const uint4 xv = g0 + i < nrb ? *(const uint4*)(xrow + (size_t)min(g0 + i, nrb - 1) * 16) : make_uint4(0, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_of(w[i]), frag_of(xv), acc, 0, 0, 0);
+        }
+    };
+    for (int g0 = 0; g0 < nrb; g0 += 2 * G) {
+        fetch_w(wB, g0 + G);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(wA, g0);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch_w(wA, g0 + 2 * G);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(wB, g0 + G);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (!fb_ok) return;
+    // accumulator register i of lane l: feature 8*(i/4) + 4*(l/32) + i%4, token l%32
+    uint16_t* ydst = h + (((size_t)slot * (N >> 3) + fb * 4) * 32 + (lane & 31)) * 8 + (lane >> 5) * 4;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const float v0 = fmaxf(acc[4 * g], 0.f), v1 = fmaxf(acc[4 * g + 1], 0.f), v2 = fmaxf(acc[4 * g + 2], 0.f),
+                    v3 = fmaxf(acc[4 * g + 3], 0.f);
+        uint2 o;
+        o.x = (uint32_t)smoe_f32_to_bf16(v0) | ((uint32_t)smoe_f32_to_bf16(v1) << 16);
+        o.y = (uint32_t)smoe_f32_to_bf16(v2) | ((uint32_t)smoe_f32_to_bf16(v3) << 16);
+        *(uint2*)(ydst + g * 32 * 8) = o;
+    }
+}
+
+template <int NEB>
+__global__ __launch_bounds__(512) void decode_first_kernel(
+    const uint16_t* __restrict__ x, const uint4* __restrict__ Wsplit, const int32_t* __restrict__ e2s,
+    int T, int d, int E, int gate_mode,
+    int32_t* __restrict__ orig_expert, float* __restrict__ orig_gate, int32_t* __restrict__ slot,
+    float* __restrict__ gate, float* __restrict__ xnorm, int K, const TailArgs tail,
+    const uint4* __restrict__ W1, uint16_t* __restrict__ h, int d_ff, const int32_t* __restrict__ phys) {
+    if (blockIdx.x == gridDim.x - 1)
+        route_mfma_body<NEB, 8, 1>(0, x, Wsplit, e2s, T, d, E, gate_mode, orig_expert, orig_gate, slot, gate, xnorm,
+                                   nullptr, K, tail);
+    else
+        dense_first_all(x, W1, T, h, d, d_ff, phys, blockIdx.x);
 }
 
 template <int NEB, int TB>
@@ -625,6 +729,54 @@ int smoe_launch_route(const smoe_layer* L, const void* x, int T, int32_t* orig_e
     if (L->cfg.dtype == SMOE_F32)
         return dispatch<float>(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, s);
     return route_bf16(L, x, T, orig_expert, orig_gate, slot, gate, xnorm, hist32, TailArgs{}, s);
+}
+
+// bf16 layers, 1 <= T <= 32, E <= 64: router (with the ranking tail) and the first FFN product of
+// every slot in one launch.  e0 / e1 (optional) take the launch's start and end.
+static size_t decode_first_lds(const smoe_config& c) {
+    const int ep = (c.E + 31) / 32 * 32;
+    const size_t lds_router = (size_t)(8 * ep * (RT + 1) + 2 * 8 * RT) * 4;      // partial logits of 8 waves + norms
+    const size_t lds_tokens = (size_t)RT * (c.d_model + 8) * 2;                  // the batch, staged for the first product
+    return lds_router > lds_tokens ? lds_router : lds_tokens;
+}
+
+bool smoe_decode_first_applies(const smoe_layer* L, int T) {
+    return L->cfg.dtype == SMOE_BF16 && T >= 1 && T <= RT && L->cfg.E <= 64 && decode_first_lds(L->cfg) <= 120 * 1024;
+}
+
+int smoe_launch_decode_first(const smoe_layer* L, const void* x, int T, int32_t* orig_expert, float* orig_gate,
+                             int32_t* slot, float* gate, float* xnorm, int32_t* count, float* gsum, float* score,
+                             int accumulate, int32_t* perm, int32_t* inv_perm, int32_t* offsets, hipStream_t s,
+                             hipEvent_t e0, hipEvent_t e1) {
+    if (!smoe_decode_first_applies(L, T)) return smoe_fail(SMOE_EINVAL, "smoe_forward: the fused decode launch does not apply");
+    const smoe_config& c = L->cfg;
+    const TailArgs tail{L->expert_norm, count, gsum, score, accumulate, perm, inv_perm, offsets};
+    const int neb = (c.E + 31) / 32;
+    const size_t lds = decode_first_lds(c);
+    const int ftiles = ((c.d_ff >> 5) + 7) / 8;
+    const dim3 grid(c.K * ftiles + 1);
+    const int32_t* phys = c.spare_slots > 0 ? L->d_phys : nullptr;
+    auto launch = [&](auto kern) -> int {
+        static int raised_on = -1;                 // raise the kernel's dynamic-LDS limit once per device
+        int dev_now = 0;
+        (void)hipGetDevice(&dev_now);
+        if (lds > 48 * 1024 && raised_on != dev_now) {
+            int rc = smoe_check_hip(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 120 * 1024),
+                                    "smoe_forward: LDS size");
+            if (rc) return rc;
+            raised_on = dev_now;
+        }
+        if (e0 && e1)
+            hipExtLaunchKernelGGL(kern, grid, dim3(512), lds, s, e0, e1, 0, (const uint16_t*)x, (const uint4*)L->d_router_split,
+                                  L->d_expert_to_slot, T, c.d_model, c.E, c.gate_mode, orig_expert, orig_gate, slot, gate, xnorm,
+                                  c.K, tail, (const uint4*)L->slot_w1, (uint16_t*)L->d_hidden, c.d_ff, phys);
+        else
+            hipLaunchKernelGGL(kern, grid, dim3(512), lds, s, (const uint16_t*)x, (const uint4*)L->d_router_split,
+                               L->d_expert_to_slot, T, c.d_model, c.E, c.gate_mode, orig_expert, orig_gate, slot, gate, xnorm,
+                               c.K, tail, (const uint4*)L->slot_w1, (uint16_t*)L->d_hidden, c.d_ff, phys);
+        return smoe_check_hip(hipGetLastError(), "smoe_forward: decode launch");
+    };
+    return neb == 1 ? launch(decode_first_kernel<1>) : launch(decode_first_kernel<2>);
 }
 
 // bf16 layers, 1 <= T <= 32: the router's single workgroup also ranks the tokens by slot

@@ -88,6 +88,15 @@ int smoe_launch_route_rank_small(const smoe_layer* L, const void* x, int T, int3
                                  float* orig_gate, int32_t* slot, float* gate, float* xnorm, int32_t* count,
                                  float* gsum, float* score, int accumulate, int32_t* perm, int32_t* inv_perm,
                                  int32_t* offsets, hipStream_t s);
+bool smoe_decode_first_applies(const smoe_layer* L, int T);
+int smoe_launch_decode_first(const smoe_layer* L, const void* x, int T, int32_t* orig_expert, float* orig_gate,
+                             int32_t* slot, float* gate, float* xnorm, int32_t* count, float* gsum, float* score,
+                             int accumulate, int32_t* perm, int32_t* inv_perm, int32_t* offsets, hipStream_t s,
+                             hipEvent_t e0, hipEvent_t e1);
+// true when the FFN of a T-token batch takes the one-tile-per-slot kernels (no sorted tiles)
+bool smoe_ffn_dense_path(const smoe_layer* L, int T);
+int smoe_launch_ffn_bf16_dense_second(const smoe_layer* L, const int32_t* slot_of, const float* gate,
+                                      const uint16_t* residual, int T, uint16_t* out, hipStream_t s);
 int smoe_launch_rank_importance(const smoe_layer* L, const int32_t* orig_expert, const float* orig_gate,
                                 const float* xnorm, const int32_t* slot, int T, int32_t* count, float* gsum,
                                 float* score, int accumulate, int32_t* perm, int32_t* inv_perm,
