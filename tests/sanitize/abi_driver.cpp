@@ -13,6 +13,11 @@
 int smoe_launch_route(const smoe_layer*, const void*, int, int32_t*, float*, int32_t*, float*, float*, int32_t*, hipStream_t) { return 0; }
 int smoe_launch_route_rank_small(const smoe_layer*, const void*, int, int32_t*, float*, int32_t*, float*, float*, int32_t*,
                                  float*, float*, int, int32_t*, int32_t*, int32_t*, hipStream_t) { return 0; }
+bool smoe_decode_first_applies(const smoe_layer*, int) { return false; }
+int smoe_launch_decode_first(const smoe_layer*, const void*, int, int32_t*, float*, int32_t*, float*, float*, int32_t*, float*, float*,
+                             int, int32_t*, int32_t*, int32_t*, hipStream_t, hipEvent_t, hipEvent_t) { return 0; }
+bool smoe_ffn_dense_path(const smoe_layer*, int) { return false; }
+int smoe_launch_ffn_bf16_dense_second(const smoe_layer*, const int32_t*, const float*, const uint16_t*, int, uint16_t*, hipStream_t) { return 0; }
 int smoe_launch_rank_importance(const smoe_layer*, const int32_t*, const float*, const float*, const int32_t*, int, int32_t*,
                                 float*, float*, int, int32_t*, int32_t*, int32_t*, hipStream_t) { return 0; }
 int smoe_launch_ffn_bf16_fused(const smoe_layer*, const uint16_t*, const int32_t*, const int32_t*, const int32_t*, const float*,
