@@ -51,7 +51,7 @@ PEAK_HBM_GBS = 8000.0
 # that summary names the kernel instances this run has just timed (smoe_describe_ffn).
 PROFILE_FILES = {
     "c3": "profiles/grouped_gemm_bf16_c3_prefill_hbm_counters.txt",
-    "c4": "profiles/dense_gemm_bf16_c4_decode_hbm_counters.txt",
+    "c4": "profiles/decode_step_c4_hbm_counters.txt",
     "c5": "profiles/grouped_gemm_bf16_c5_prefill_hbm_counters.txt",
 }
 
