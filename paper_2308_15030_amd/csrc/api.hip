@@ -7,6 +7,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <algorithm>
+#include <atomic>
 #include <new>
 #include <numeric>
 
@@ -75,6 +76,17 @@ smoe_ws_layout smoe_ws_plan(const smoe_config& c) {
     return w;
 }
 
+// slot bytes of every live layer (see smoe_weights_outgrow_cache)
+static std::atomic<long long> g_live_slot_bytes{0};
+static long long layer_slot_bytes(const smoe_config& c) {
+    return 2ll * (c.K + c.spare_slots) * c.d_model * c.d_ff * (long long)smoe_elem_size(c.dtype);
+}
+
+bool smoe_weights_outgrow_cache() {
+    constexpr long long kCacheable = 192ll << 20;          // three quarters of the 256 MB Infinity Cache
+    return g_live_slot_bytes.load(std::memory_order_relaxed) > kCacheable;
+}
+
 extern "C" {
 
 const char* smoe_last_error(void) { return g_err; }
@@ -111,12 +123,14 @@ int smoe_create(const smoe_config* cfg, smoe_layer_t** out) {
         int a = -1, b = -1;
         if (sscanf(env, "%d,%d", &a, &b) == 2 && a >= 0 && b >= 0) { L->ffn_variant[0] = a; L->ffn_variant[1] = b; }
     }
+    g_live_slot_bytes += layer_slot_bytes(c);
     *out = L;
     return SMOE_OK;
 }
 
 int smoe_destroy(smoe_layer_t* layer) {
     if (!layer) return smoe_fail(SMOE_EINVAL, "smoe_destroy: null handle");
+    g_live_slot_bytes -= layer_slot_bytes(layer->cfg);
     for (auto& st : layer->staged) if (st.done) (void)hipEventDestroy(st.done);
     for (hipEvent_t e : layer->event_pool) (void)hipEventDestroy(e);
     for (hipEvent_t e : layer->released) if (e) (void)hipEventDestroy(e);

@@ -752,8 +752,9 @@ __global__ __launch_bounds__(NWV * 64) void small_gemm_bf16(
 // nobody was routed to leaves after one group of weight loads.
 // The hidden activations are kept per slot: h[slot][feature/8][token] units of
 // 8 features (fragment order with the token index as the row).
-template <int NWV, int KSPLIT, bool FIRST>
-__global__ __launch_bounds__(NWV * 64) void dense_gemm_bf16(
+// STREAM: the weight loads are marked non-temporal (see smoe_weights_outgrow_cache).
+template <int NWV, int KSPLIT, bool FIRST, bool STREAM>
+__device__ __forceinline__ void dense_gemm_body(
     const uint16_t* __restrict__ X, const uint4* __restrict__ Wp, const int32_t* __restrict__ slot_of,
     int T, uint16_t* __restrict__ Y, int R, int N, const int32_t* __restrict__ phys,
     const float* __restrict__ gate, const uint16_t* __restrict__ residual) {
@@ -775,7 +776,10 @@ __global__ __launch_bounds__(NWV * 64) void dense_gemm_bf16(
     uint4 wA[G], xA[G], wB[G], xB[G];
     auto fetch_w = [&](uint4 (&w)[G], int g0) {
 #pragma unroll
-        for (int i = 0; i < G; ++i) w[i] = wp[(size_t)max(min(g0 + i, kb_hi - 1), 0) * 64];   // past the end: reloaded, not used
+        for (int i = 0; i < G; ++i) {                      // past the end: reloaded, not used
+            const uint4* src = wp + (size_t)max(min(g0 + i, kb_hi - 1), 0) * 64;
+            w[i] = STREAM ? smoe_load_stream(src) : *src;
+        }
     };
     fetch_w(wA, kb_lo);                                    // on its way before anything else is known
     const bool mine = tok < T && slot_of[min(tok, T - 1)] == slot;
@@ -858,6 +862,22 @@ __global__ __launch_bounds__(NWV * 64) void dense_gemm_bf16(
         o.y = (uint32_t)smoe_f32_to_bf16(v2) | ((uint32_t)smoe_f32_to_bf16(v3) << 16);
         *(uint2*)(ydst + (FIRST ? g * 32 * 8 : g * 8)) = o;
     }
+}
+
+// Two kernels with one body: the second streams its weights past the caches.
+#define SMOE_DENSE_GEMM_PARAMS                                                                              \
+    const uint16_t* __restrict__ X, const uint4* __restrict__ Wp, const int32_t* __restrict__ slot_of, int T,  \
+    uint16_t* __restrict__ Y, int R, int N, const int32_t* __restrict__ phys, const float* __restrict__ gate,  \
+    const uint16_t* __restrict__ residual
+
+template <int NWV, int KSPLIT, bool FIRST>
+__global__ __launch_bounds__(NWV * 64) void dense_gemm_bf16(SMOE_DENSE_GEMM_PARAMS) {
+    dense_gemm_body<NWV, KSPLIT, FIRST, false>(X, Wp, slot_of, T, Y, R, N, phys, gate, residual);
+}
+
+template <int NWV, int KSPLIT, bool FIRST>
+__global__ __launch_bounds__(NWV * 64) void dense_gemm_stream_bf16(SMOE_DENSE_GEMM_PARAMS) {
+    dense_gemm_body<NWV, KSPLIT, FIRST, true>(X, Wp, slot_of, T, Y, R, N, phys, gate, residual);
 }
 
 template <int NWV, int KSPLIT, bool FIRST>
@@ -969,9 +989,11 @@ int smoe_describe_ffn_bf16(const smoe_layer* L, int T, int fused, char* out, siz
         const int R = first ? L->cfg.d_model : L->cfg.d_ff;
         const char* shape = nullptr;                       // AF, MAXB, NW, BKT, PD, OCC of launch_variant
         std::string name;
+        const std::string st = smoe_weights_outgrow_cache() ? "_stream" : "";
         if (fused && T <= 32 && v[0] == 5 && v[1] == 6 && smoe_decode_first_applies(L, T))
-            name = first ? (L->cfg.E <= 32 ? "decode_first_kernel<1>" : "decode_first_kernel<2>") : "dense_gemm_bf16<4, 4, false>";
-        else if (fused && T <= 32 && v[0] == 5 && v[1] == 6) name = first ? "dense_gemm_bf16<6, 1, true>" : "dense_gemm_bf16<4, 4, false>";
+            name = first ? "decode_first" + st + (L->cfg.E <= 32 ? "_kernel<1>" : "_kernel<2>") : "dense_gemm" + st + "_bf16<4, 4, false>";
+        else if (fused && T <= 32 && v[0] == 5 && v[1] == 6)
+            name = "dense_gemm" + st + (first ? "_bf16<6, 1, true>" : "_bf16<4, 4, false>");
         else if (v[i] == 5) name = std::string("small_gemm_bf16<4, 1, ") + (first ? "true>" : "false>");
         else if (v[i] == 6) name = std::string("small_gemm_bf16<4, 4, ") + (first ? "true>" : "false>");
         else if (R % 64 != 0) shape = "1, 4, 4, 32, ";
@@ -1019,9 +1041,14 @@ int smoe_launch_ffn_bf16_dense_second(const smoe_layer* L, const int32_t* slot_o
                                       const uint16_t* residual, int T, uint16_t* out, hipStream_t s) {
     const smoe_config& c = L->cfg;
     const int32_t* phys = c.spare_slots > 0 ? L->d_phys : nullptr;
-    smoe_launch_timed(dense_gemm_bf16<4, 4, false>, dim3(c.K * (c.d_model >> 5)), dim3(256), s, L->prof_ev[2], L->prof_ev[3],
-                      (const uint16_t*)L->d_hidden, (const uint4*)L->slot_w2, slot_of, T, out, c.d_ff, c.d_model, phys, gate,
-                      residual);
+    if (smoe_weights_outgrow_cache())
+        smoe_launch_timed(dense_gemm_stream_bf16<4, 4, false>, dim3(c.K * (c.d_model >> 5)), dim3(256), s, L->prof_ev[2],
+                          L->prof_ev[3], (const uint16_t*)L->d_hidden, (const uint4*)L->slot_w2, slot_of, T, out, c.d_ff,
+                          c.d_model, phys, gate, residual);
+    else
+        smoe_launch_timed(dense_gemm_bf16<4, 4, false>, dim3(c.K * (c.d_model >> 5)), dim3(256), s, L->prof_ev[2],
+                          L->prof_ev[3], (const uint16_t*)L->d_hidden, (const uint4*)L->slot_w2, slot_of, T, out, c.d_ff,
+                          c.d_model, phys, gate, residual);
     return smoe_check_hip(hipGetLastError(), "smoe_forward: FFN launch");
 }
 
@@ -1037,12 +1064,21 @@ int smoe_launch_ffn_bf16_fused(const smoe_layer* L, const uint16_t* x, const int
     const int32_t* phys = L->cfg.spare_slots > 0 ? L->d_phys : nullptr;   // identity without spare slots
     if (T <= 32 && v1 == 5 && v2 == 6) {      // the whole batch is one token block: no sorted tiles needed
         const int nfb1 = c.d_ff >> 5, nfb2 = c.d_model >> 5;
-        smoe_launch_timed(dense_gemm_bf16<6, 1, true>, dim3(c.K * ((nfb1 + 5) / 6)), dim3(384), s, L->prof_ev[0],
-                          L->prof_ev[1], x, (const uint4*)L->slot_w1, slot_of, T, h, c.d_model, c.d_ff,
-                          phys, (const float*)nullptr, (const uint16_t*)nullptr);
-        smoe_launch_timed(dense_gemm_bf16<4, 4, false>, dim3(c.K * nfb2), dim3(256), s, L->prof_ev[2],
-                          L->prof_ev[3], (const uint16_t*)h, (const uint4*)L->slot_w2, slot_of, T, out, c.d_ff,
-                          c.d_model, phys, gate, residual);
+        if (smoe_weights_outgrow_cache()) {
+            smoe_launch_timed(dense_gemm_stream_bf16<6, 1, true>, dim3(c.K * ((nfb1 + 5) / 6)), dim3(384), s, L->prof_ev[0],
+                              L->prof_ev[1], x, (const uint4*)L->slot_w1, slot_of, T, h, c.d_model, c.d_ff,
+                              phys, (const float*)nullptr, (const uint16_t*)nullptr);
+            smoe_launch_timed(dense_gemm_stream_bf16<4, 4, false>, dim3(c.K * nfb2), dim3(256), s, L->prof_ev[2],
+                              L->prof_ev[3], (const uint16_t*)h, (const uint4*)L->slot_w2, slot_of, T, out, c.d_ff,
+                              c.d_model, phys, gate, residual);
+        } else {
+            smoe_launch_timed(dense_gemm_bf16<6, 1, true>, dim3(c.K * ((nfb1 + 5) / 6)), dim3(384), s, L->prof_ev[0],
+                              L->prof_ev[1], x, (const uint4*)L->slot_w1, slot_of, T, h, c.d_model, c.d_ff,
+                              phys, (const float*)nullptr, (const uint16_t*)nullptr);
+            smoe_launch_timed(dense_gemm_bf16<4, 4, false>, dim3(c.K * nfb2), dim3(256), s, L->prof_ev[2],
+                              L->prof_ev[3], (const uint16_t*)h, (const uint4*)L->slot_w2, slot_of, T, out, c.d_ff,
+                              c.d_model, phys, gate, residual);
+        }
         return smoe_check_hip(hipGetLastError(), "smoe_forward: FFN launch");
     }
     const FuseArgs gather{phys, perm, nullptr, nullptr}, scatter{phys, perm, gate, residual};

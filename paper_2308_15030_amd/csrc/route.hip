@@ -540,6 +540,8 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
 // 8 waves per workgroup, one 32-feature block per wave; the token operands come from LDS
 // (row pitch d_model + 8 elements: conflict-free 16-byte reads), so the vector-memory pipe
 // carries nothing but the 1-KiB weight loads, 16 of them in flight per wave.
+// STREAM: the weight loads are marked non-temporal (see smoe_weights_outgrow_cache).
+template <bool STREAM>
 __device__ __forceinline__ void dense_first_all(const uint16_t* __restrict__ x, const uint4* __restrict__ Wp,
                                                 int T, uint16_t* __restrict__ h, int R, int N,
                                                 const int32_t* __restrict__ phys, int block) {
@@ -556,7 +558,10 @@ __device__ __forceinline__ void dense_first_all(const uint16_t* __restrict__ x, 
     uint4 wA[G], wB[G];
     auto fetch_w = [&](uint4 (&w)[G], int g0) {
 #pragma unroll
-        for (int i = 0; i < G; ++i) w[i] = wp[(size_t)min(g0 + i, nrb - 1) * 64];      // past the end: reloaded, not used
+        for (int i = 0; i < G; ++i) {                      // past the end: reloaded, not used
+            const uint4* src = wp + (size_t)min(g0 + i, nrb - 1) * 64;
+            w[i] = STREAM ? smoe_load_stream(src) : *src;
+        }
     };
     fetch_w(wA, 0);                                        // on their way while the tokens are staged
     const int cpr = R >> 3;                                // 16-byte pieces per token row
@@ -603,18 +608,32 @@ __device__ __forceinline__ void dense_first_all(const uint16_t* __restrict__ x, 
     }
 }
 
-template <int NEB>
-__global__ __launch_bounds__(512) void decode_first_kernel(
-    const uint16_t* __restrict__ x, const uint4* __restrict__ Wsplit, const int32_t* __restrict__ e2s,
-    int T, int d, int E, int gate_mode,
-    int32_t* __restrict__ orig_expert, float* __restrict__ orig_gate, int32_t* __restrict__ slot,
-    float* __restrict__ gate, float* __restrict__ xnorm, int K, const TailArgs tail,
-    const uint4* __restrict__ W1, uint16_t* __restrict__ h, int d_ff, const int32_t* __restrict__ phys) {
+#define SMOE_DECODE_FIRST_PARAMS                                                                            \
+    const uint16_t* __restrict__ x, const uint4* __restrict__ Wsplit, const int32_t* __restrict__ e2s,          \
+    int T, int d, int E, int gate_mode, int32_t* __restrict__ orig_expert, float* __restrict__ orig_gate,       \
+    int32_t* __restrict__ slot, float* __restrict__ gate, float* __restrict__ xnorm, int K, const TailArgs tail, \
+    const uint4* __restrict__ W1, uint16_t* __restrict__ h, int d_ff, const int32_t* __restrict__ phys
+
+template <int NEB, bool STREAM>
+__device__ __forceinline__ void decode_first_body(SMOE_DECODE_FIRST_PARAMS) {
     if (blockIdx.x == gridDim.x - 1)
         route_mfma_body<NEB, 8, 1>(0, x, Wsplit, e2s, T, d, E, gate_mode, orig_expert, orig_gate, slot, gate, xnorm,
                                    nullptr, K, tail);
     else
-        dense_first_all(x, W1, T, h, d, d_ff, phys, blockIdx.x);
+        dense_first_all<STREAM>(x, W1, T, h, d, d_ff, phys, blockIdx.x);
+}
+
+// Two kernels with one body: the second streams its weights past the caches.
+template <int NEB>
+__global__ __launch_bounds__(512) void decode_first_kernel(SMOE_DECODE_FIRST_PARAMS) {
+    decode_first_body<NEB, false>(x, Wsplit, e2s, T, d, E, gate_mode, orig_expert, orig_gate, slot, gate, xnorm, K, tail,
+                                  W1, h, d_ff, phys);
+}
+
+template <int NEB>
+__global__ __launch_bounds__(512) void decode_first_stream_kernel(SMOE_DECODE_FIRST_PARAMS) {
+    decode_first_body<NEB, true>(x, Wsplit, e2s, T, d, E, gate_mode, orig_expert, orig_gate, slot, gate, xnorm, K, tail,
+                                 W1, h, d_ff, phys);
 }
 
 template <int NEB, int TB>
@@ -757,14 +776,22 @@ int smoe_launch_decode_first(const smoe_layer* L, const void* x, int T, int32_t*
     const dim3 grid(c.K * ftiles + 1);
     const int32_t* phys = c.spare_slots > 0 ? L->d_phys : nullptr;
     auto launch = [&](auto kern) -> int {
-        static int raised_on = -1;                 // raise the kernel's dynamic-LDS limit once per device
+        // raise the kernel's dynamic-LDS limit once per kernel and device (the four instances share
+        // one function type, hence one instance of this lambda: the table is keyed by the pointer)
+        static const void* raised_kern[8];
+        static int raised_dev[8];
+        static int nraised = 0;
         int dev_now = 0;
         (void)hipGetDevice(&dev_now);
-        if (lds > 48 * 1024 && raised_on != dev_now) {
-            int rc = smoe_check_hip(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 120 * 1024),
-                                    "smoe_forward: LDS size");
-            if (rc) return rc;
-            raised_on = dev_now;
+        if (lds > 48 * 1024) {
+            bool done = false;
+            for (int i = 0; i < nraised; ++i) done |= raised_kern[i] == (const void*)kern && raised_dev[i] == dev_now;
+            if (!done) {
+                int rc = smoe_check_hip(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 120 * 1024),
+                                        "smoe_forward: LDS size");
+                if (rc) return rc;
+                if (nraised < 8) { raised_kern[nraised] = (const void*)kern; raised_dev[nraised] = dev_now; ++nraised; }
+            }
         }
         if (e0 && e1)
             hipExtLaunchKernelGGL(kern, grid, dim3(512), lds, s, e0, e1, 0, (const uint16_t*)x, (const uint4*)L->d_router_split,
@@ -776,6 +803,8 @@ int smoe_launch_decode_first(const smoe_layer* L, const void* x, int T, int32_t*
                                c.K, tail, (const uint4*)L->slot_w1, (uint16_t*)L->d_hidden, c.d_ff, phys);
         return smoe_check_hip(hipGetLastError(), "smoe_forward: decode launch");
     };
+    if (smoe_weights_outgrow_cache())
+        return neb == 1 ? launch(decode_first_stream_kernel<1>) : launch(decode_first_stream_kernel<2>);
     return neb == 1 ? launch(decode_first_kernel<1>) : launch(decode_first_kernel<2>);
 }
 

@@ -85,3 +85,44 @@ def test_decode_with_updates(fused):
     print(f"decode: {swaps} experts swapped over {STEPS // cfg.period} updates; "
           f"hit rate {np.mean(hits[:cfg.period]):.2f} -> {np.mean(hits[cfg.period:]):.2f}", flush=True)
     L.close()
+
+
+def test_decode_streaming_loads_same_bits():
+    """Once the expert slots of the live layers outgrow the Infinity Cache the decode kernels
+    read their weights with non-temporal loads (other kernel instances, same arithmetic): the
+    step's outputs, choices and sums must keep their bits."""
+    cfg = wl.CONFIGS["c4"]
+    from paper_2308_15030_amd import binding as b
+    c = Case(cfg, bank_experts=range(cfg.K), x=np.zeros((cfg.T, cfg.d_model), np.uint16))
+    L, T = c.L, cfg.T
+    xs = wl.decode_stream(cfg, 4)
+    d_xs = to_dev(xs.reshape(4 * T, cfg.d_model)).view(4, T, cfg.d_model)
+
+    def run():
+        got = []
+        for step in range(4):
+            out = L.forward_fused(d_xs[step], T, accumulate=0 if step == 0 else 1, residual=d_xs[step])
+            torch.cuda.synchronize()
+            got.append([to_host(out).copy(), to_host(L.slot).copy(), to_host(L.perm).copy(), to_host(L.offsets).copy(),
+                        to_host(L.count).copy(), to_host(L.gsum).copy(), to_host(L.score).copy()])
+        return got
+
+    assert "_stream" not in b.smoe_describe_ffn(L.handle, T, True)
+    cached = run()
+    ballast = []
+    while "_stream" not in b.smoe_describe_ffn(L.handle, T, True):
+        assert len(ballast) < 4, "four more layers of this shape are 600 MB: the switch should have happened"
+        ballast.append(b.Layer(cfg.E, cfg.K, cfg.d_model, cfg.d_ff, T, cfg.dtype, 0,
+                               router_w=torch.from_numpy(c.Wr), device=c.dev))
+    streamed = run()
+    for step, (a, s) in enumerate(zip(cached, streamed)):
+        for u, v in zip(a, s):
+            assert np.array_equal(u, v), step
+    # and against the oracle, on the last step
+    ref = oracle.layer_forward(xs[3], c.Wr, *c.slot_weights_host(), c.e2s, residual=xs[3])
+    ok = ~ref["ambiguous"]
+    assert max_abs_rel(values(streamed[3][0], cfg.dtype)[ok], values(ref["out"], cfg.dtype)[ok]) <= 2e-2
+    for lay in ballast:
+        lay.close()
+    assert "_stream" not in b.smoe_describe_ffn(L.handle, T, True)
+    L.close()
