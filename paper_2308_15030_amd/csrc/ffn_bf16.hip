@@ -476,6 +476,9 @@ __device__ __forceinline__ void run_tile(const uint16_t* __restrict__ X, const u
             uint4 rs[CH];
 #pragma unroll
             for (int j = 0; j < CH; ++j) {                // residual pieces not fetched earlier are asked for first
+                // the last group is short when NP is not a multiple of CH: a piece past NP would belong
+                // to a row below the tile, whose entry of the row table is stale
+                if (i0 + j >= NP) { prow[j] = -1; pcol[j] = 0; rs[j] = make_uint4(0, 0, 0, 0); continue; }
                 const int idx = tid + (i0 + j) * THREADS, r = idx / CPR8, c = idx % CPR8;
                 pcol[j] = col0 + c * 8;
                 prow[j] = pcol[j] < N ? orow[r] : -1;
@@ -924,13 +927,11 @@ void launch_gemm(const uint16_t* X, const void* Wp, const int32_t* offsets, int 
                           (const uint4*)Wp, offsets, nslots, T, Y, R, N, fz);
 }
 
-// The tile shapes launch_variant knows (every one of them is chosen somewhere by pick_variants).
-// The 256 x 256 tile (10) is a first-product shape only: as the second product its instance
-// needs 139 KB of LDS for the output turn plus 85 spilled registers, and the one run of it at
-// the Switch-base-64 shape ended in a GPU fault whose cause has not been found, so the
-// override refuses it there.
-constexpr bool is_variant(int v, bool first) {
-    return v == 1 || v == 3 || v == 4 || v == 5 || v == 6 || v == 8 || (v == 10 && first);
+// The tile shapes launch_variant knows (every one of them is chosen somewhere by pick_variants,
+// except the 256 x 256 tile as the second product: 139 KB of LDS for the output turn and 85
+// spilled registers make it slow, and it is there for the override only).
+constexpr bool is_variant(int v) {
+    return v == 1 || v == 3 || v == 4 || v == 5 || v == 6 || v == 8 || v == 10;
 }
 
 template <bool FIRST>
@@ -946,9 +947,7 @@ void launch_variant(int v, const uint16_t* X, const void* Wp, const int32_t* off
         case 3: launch_gemm<1, 2, 4, 64, 1, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  //  64 x 128
         case 4: launch_gemm<1, 1, 4, 64, 3, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  //  32 x 128
         case 8: launch_gemm<1, 4, 8, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  // 128 x 256, 8 waves
-        case 10:                                                                                                    // 256 x 256, 8 waves
-            if constexpr (FIRST) { launch_gemm<1, 8, 8, 64, 1, 2, true>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break; }
-            [[fallthrough]];                                        // (never reached: pick_variants refuses it)
+        case 10: launch_gemm<1, 8, 8, 64, 1, 2, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;  // 256 x 256, 8 waves
         case 5: launch_small<4, 1, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;   // 32 x 128, streaming
         case 6: launch_small<4, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;   // 32 x 32, reduction split 4 ways
         default: launch_small<4, 4, FIRST>(X, Wp, offsets, nslots, Y, R, N, T, fz, s, e0, e1); break;
@@ -969,7 +968,7 @@ void pick_variants(const smoe_layer* L, int T, int& v1, int& v2) {
     else if (per_slot >= 28) { v1 = 3; v2 = 4; }
     else if (per_slot >= 6) { v1 = 4; v2 = 6; }
     else { v1 = 5; v2 = 6; }             // decode: a few tokens per slot, weight streaming
-    if (is_variant(L->ffn_variant[0], true) && is_variant(L->ffn_variant[1], false)) {
+    if (is_variant(L->ffn_variant[0]) && is_variant(L->ffn_variant[1])) {
         v1 = L->ffn_variant[0];
         v2 = L->ffn_variant[1];
     }
