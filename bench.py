@@ -446,12 +446,34 @@ def main():
                             first_launch_streamed_GBs=round(streamed / g1.mean() / 1e9, 1),
                             second_launch_GBs=round(bytes_launch / g2.mean() / 1e9, 1))
 
+    if roof is not None:
+        # What a launch that only READS one product's weights costs on this GPU: the library's plain
+        # streaming kernel over the K slots of each layer in turn (first matrices, then second), same
+        # cache state as the step itself (one layer stays in the Infinity Cache, a stack does not).
+        reps = 10
+        lay0 = layers[0]
+        for which in (0, 1):                                   # warm-up
+            for lay in layers:
+                b.smoe_profile_stream_read(lay.handle, which)
+        b.smoe_profile_begin(lay0.handle)
+        for _ in range(reps):
+            for lay in layers:
+                for which in (0, 1):
+                    b.smoe_profile_stream_read(lay.handle, which)
+        us = b.smoe_profile_end(lay0.handle) / (reps * len(layers) * 2)
+        nbytes = 2.0 * cfg.K * cfg.d_model * cfg.d_ff
+        roof["plain_read_of_all_slots"] = {"bytes_per_launch": nbytes, "us_per_launch": round(us, 2),
+                                           "GBs": round(nbytes / us / 1e3, 1),
+                                           "frac_of_hbm_peak": round(nbytes / us / 1e3 / PEAK_HBM_GBS, 4),
+                                           "note": "smoe_profile_stream_read back to back: the time of a launch that moves one "
+                                                   "product's K weight matrices and does no arithmetic"}
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
         Wr, W1, W2 = host0
         if not decode:
-            reps = 3 if args.workload != "c5" else 1
+            reps = 20 if args.workload != "c5" else 2       # about 10 s of host work
             t1 = time.perf_counter()
             for _ in range(reps):
                 oracle.layer_forward(x_host, Wr, W1[:cfg.K], W2[:cfg.K], e2s0)
@@ -460,7 +482,7 @@ def main():
                    "cpu_model": cpu_model(), "kind": "oracle", "sample": f"{reps} x one full layer (layer 0) of {cfg.name}, all {T} tokens "
                                                f"each, {tc:.2f}s wall"}
         else:
-            n = min(steps, 64)
+            n = min(steps, 256)
             t1 = time.perf_counter()
             for i in range(n):
                 oracle.layer_forward(xs_host[i], Wr, W1[:cfg.K], W2[:cfg.K], e2s0)

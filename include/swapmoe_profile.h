@@ -47,6 +47,16 @@ int smoe_profile_end(smoe_layer_t* layer, void* stream, float* elapsed_us /*host
  * the curve never rises).  Host arrays; negative return = smoe_status. */
 int smoe_period_inflection(const float* latency_us /*host*/, int n, float tolerance);
 
+/* Calibration for the rooflines this library is measured against (not part of
+ * the paper's method): enqueues a kernel that does nothing but read the first K
+ * slots of the first (which = 0) or second (which = 1) slot array once --
+ * K * d_model * d_ff * sizeof(dtype) bytes, the bytes the weight-streaming
+ * kernels of a decode step read when every slot is active -- with plain
+ * coalesced loads.  Bracket it with smoe_profile_begin / _end: the elapsed time
+ * is what a launch that moves these bytes costs on this GPU with no arithmetic
+ * at all.  SMOE_ESTATE before smoe_bind. */
+int smoe_profile_stream_read(smoe_layer_t* layer, int which, void* stream);
+
 /* Measurement aid (not part of the paper's method): HIP events for the NEXT
  * smoe_expert_ffn (or smoe_forward) call on this handle.  The call attaches
  * them to its two product kernels' own dispatches: g1_begin / g1_end take the

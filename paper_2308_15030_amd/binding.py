@@ -66,6 +66,7 @@ _SIGS = {
     "smoe_profile_end": (C.c_int, [_vp, _vp, C.POINTER(C.c_float)]),
     "smoe_period_inflection": (C.c_int, [_vp, _i, C.c_float]),
     "smoe_describe_ffn": (C.c_int, [_vp, _i, _i, C.c_char_p, C.c_size_t]),
+    "smoe_profile_stream_read": (C.c_int, [_vp, _i, _vp]),
     "smoe_forward": (C.c_int, [_vp, _vp, _i, _vp, _vp, _i] + [_vp] * 12),
 }
 EXPORTS = tuple(_SIGS)
@@ -230,6 +231,10 @@ def smoe_profile_end(layer, stream=None) -> float:
     us = C.c_float(0.0)
     _check(_lib.smoe_profile_end(layer, _stream(stream), C.byref(us)))
     return float(us.value)
+
+
+def smoe_profile_stream_read(layer, which, stream=None):
+    _check(_lib.smoe_profile_stream_read(layer, int(which), _stream(stream)))
 
 
 def smoe_period_inflection(latency_us, tolerance) -> int:

@@ -85,6 +85,13 @@ int smoe_profile_begin(smoe_layer_t* L, void* stream) {
     return smoe_check_hip(hipEventRecord(L->bracket[0], (hipStream_t)stream), "smoe_profile_begin: record");
 }
 
+int smoe_profile_stream_read(smoe_layer_t* L, int which, void* stream) {
+    if (!L) return smoe_fail(SMOE_EINVAL, "smoe_profile_stream_read: null handle");
+    if (which != 0 && which != 1) return smoe_fail(SMOE_EINVAL, "smoe_profile_stream_read: which=%d is neither 0 nor 1", which);
+    if (!L->workspace) return smoe_fail(SMOE_ESTATE, "smoe_profile_stream_read: smoe_bind has not been called");
+    return smoe_launch_stream_read(L, which, (hipStream_t)stream);
+}
+
 int smoe_profile_end(smoe_layer_t* L, void* stream, float* elapsed_us) {
     if (!L || !elapsed_us) return smoe_fail(SMOE_EINVAL, "smoe_profile_end: null argument");
     if (!L->bracket_open) return smoe_fail(SMOE_ESTATE, "smoe_profile_end: no smoe_profile_begin before it");

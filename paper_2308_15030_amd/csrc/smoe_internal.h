@@ -100,6 +100,8 @@ int smoe_launch_decode_first(const smoe_layer* L, const void* x, int T, int32_t*
 // one layer (151 MB, stays cached from step to step) is 15 % slower with such loads, six
 // layers (906 MB, never cached) are 7 % faster.
 bool smoe_weights_outgrow_cache();
+// plain read of the first K slots of slot_w1 (which = 0) or slot_w2 (1): see smoe_profile_stream_read
+int smoe_launch_stream_read(const smoe_layer* L, int which, hipStream_t s);
 bool smoe_ffn_dense_path(const smoe_layer* L, int T);
 int smoe_launch_ffn_bf16_dense_second(const smoe_layer* L, const int32_t* slot_of, const float* gate,
                                       const uint16_t* residual, int T, uint16_t* out, hipStream_t s);

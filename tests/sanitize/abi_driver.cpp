@@ -37,6 +37,7 @@ int smoe_launch_set_map(const smoe_layer*, int, int, int, int, hipStream_t) { re
 int smoe_launch_expert_norm(const smoe_layer*, const void*, const void*, int, float*, hipStream_t) { return 0; }
 int smoe_launch_clear_maps(const smoe_layer*, hipStream_t) { return 0; }
 int smoe_launch_split_router(const smoe_layer*, hipStream_t) { return 0; }
+int smoe_launch_stream_read(const smoe_layer*, int, hipStream_t) { return 0; }
 
 #define EXPECT(call, want) do { int rc_ = (call); if (rc_ != (want)) { printf("line %d: got %d, want %d (%s)\n", __LINE__, rc_, (int)(want), smoe_last_error()); return 1; } } while (0)
 
@@ -93,6 +94,8 @@ int main() {
     EXPECT(smoe_profile_end(h, nullptr, &us), SMOE_ESTATE);
     char buf[128];
     EXPECT(smoe_describe_ffn(h, 4, 1, buf, sizeof buf), SMOE_OK);
+    EXPECT(smoe_profile_stream_read(h, 2, nullptr), SMOE_EINVAL);
+    EXPECT(smoe_profile_stream_read(h, 1, nullptr), SMOE_OK);
     EXPECT(smoe_destroy(h), SMOE_OK);
     EXPECT(smoe_destroy(nullptr), SMOE_EINVAL);
     printf("ok\n");

@@ -122,6 +122,21 @@ def test_profile_and_period_sweep():
     assert 5.0 < layer_us < 500.0 and 1.0 < load_us < 500.0
     with pytest.raises(b.SmoeError):
         b.smoe_profile_end(L.handle)                         # no begin before it
+    # the streaming calibration: reads the slots, changes nothing, and takes what a read of
+    # K * d * f * 2 bytes can take on this chip (between its 8 TB/s peak and a tenth of it)
+    ref_out = to_host(L.forward_fused(d_xs[0], T, accumulate=0)).copy()
+    for which in (0, 1):
+        b.smoe_profile_stream_read(L.handle, which)
+    b.smoe_profile_begin(L.handle)
+    for _ in range(8):
+        for which in (0, 1):
+            b.smoe_profile_stream_read(L.handle, which)
+    read_us = b.smoe_profile_end(L.handle) / 16
+    nbytes = cfg.K * cfg.d_model * cfg.d_ff * 2
+    assert nbytes / 8e12 * 1e6 < read_us < nbytes / 0.8e12 * 1e6, read_us
+    assert np.array_equal(to_host(L.forward_fused(d_xs[0], T, accumulate=0)), ref_out)
+    with pytest.raises(b.SmoeError):
+        b.smoe_profile_stream_read(L.handle, 2)
     # period sweep, lowest update frequency first
     periods, lat = [32, 8, 2, 1], []
     for p in periods:
@@ -135,6 +150,6 @@ def test_profile_and_period_sweep():
     k = b.smoe_period_inflection(lat, 0.25)
     assert 0 <= k < len(periods)
     assert lat[-1] > lat[0], "updating after every step must cost more than updating every 32"
-    print(f"profile: layer {layer_us:.1f} us, expert load {load_us:.1f} us, sweep {dict(zip(periods, np.round(lat, 1)))} "
+    print(f"profile: layer {layer_us:.1f} us, expert load {load_us:.1f} us, plain read of one product's slots {read_us:.1f} us, sweep {dict(zip(periods, np.round(lat, 1)))} "
           f"-> period {periods[k]}", flush=True)
     L.close()
