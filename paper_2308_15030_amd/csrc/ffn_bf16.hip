@@ -58,17 +58,16 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
 // Work enumeration of the tiled kernel.  A work item is (row tile, feature
 // tile); the row tiles of all slots form one list in slot order, ceil(len/bt)
 // per slot.  Workgroups are dealt to the 8 XCDs round-robin by their linear id,
-// so workgroup wg runs on XCD wg % 8.  The items
-// (row tile mt, feature tile ft) are numbered g = mt * ftiles + ft, and die x
-// owns the x-th eighth of that list: the dies' shares differ by at most one
+// so workgroup wg runs on XCD wg % 8.  The items are numbered slot by slot --
+// inside a slot with the feature tile fastest (second product: g = mt * ftiles
+// + ft) or with the row tile fastest (first product, see the kernel) -- and die
+// x owns the x-th eighth of that list: the dies' shares differ by at most one
 // item (a split by whole row tiles can leave one die with a fifth more work and
-// a whole extra round of tiles), a share still covers few slots, and on a die
-// the feature tile varies fastest, so the workgroups that run together stream
-// many different weight tiles at once (more bytes in flight to HBM) while they
-// share the die's few token tiles through its L2.  The grid holds as many
-// workgroups as the chip keeps resident; the j-th workgroup of a die takes the
-// die's items j, j + n, j + 2n, ... (n workgroups per die).  Each workgroup
-// builds the per-slot tables once, in LDS.
+// a whole extra round of tiles) and a share still covers few slots, whose
+// token or weight tiles the die's workgroups share through its L2.  The grid
+// holds as many workgroups as the chip keeps resident; the j-th workgroup of a
+// die takes the die's items j, j + n, j + 2n, ... (n workgroups per die).  Each
+// workgroup builds the per-slot tables once, in LDS.
 constexpr int MAX_SLOTS = 256;            // K <= E <= 256 by the C ABI
 
 struct ItemMap {
