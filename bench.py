@@ -168,10 +168,13 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--decode-layers", type=int, default=1,
                     help="c4 only: independent layers per decode step (6 exceeds the 256 MB Infinity Cache)")
-    ap.add_argument("--updates", default="sync", choices=["sync", "async", "none"],
-                    help="c4 only: how the resident set follows the scores. sync: all changes applied at the "
-                         "period boundary on the compute stream; async: smoe_update_begin/tick, loads on a second "
-                         "stream into a spare slot, spread over the following steps; none: never updated")
+    ap.add_argument("--updates", default=None, choices=["device", "sync", "async", "none"],
+                    help="c4 only: how the resident set follows the scores. device (default with the bank in device "
+                         "memory): smoe_update_on_device, the update rule and the slot loads run on the GPU behind the "
+                         "period's last step, no read-back; sync (default otherwise): the scores are read back, the host "
+                         "applies the rule and reloads the changed slots before the next step; async: "
+                         "smoe_update_begin/tick, loads on a second stream into a spare slot, spread over the following "
+                         "steps; none: never updated")
     ap.add_argument("--policy", default="importance", choices=["importance", "count", "static", "lru"],
                     help="c4 only: what ranks the experts at an update. importance: the Eq. 1 score; count: tokens "
                          "per expert (the 'simple scheduling' ablation); static: the K experts of largest |E_i|, "
@@ -288,6 +291,8 @@ def main():
         xs_host = wl.decode_stream(cfg, warmup + steps)
         xs = dev_t(xs_host.reshape(-1, cfg.d_model), dev).view(warmup + steps, T, cfg.d_model)
 
+        if args.updates is None:                     # the rule on the GPU when the bank is there, else on the host
+            args.updates = "device" if (args.bank == "device" and args.policy in ("importance", "count")) else "sync"
         if args.policy == "lru" and args.updates != "sync":
             sys.exit("bench.py: --policy lru needs --updates sync")
         if args.policy == "static":                  # the K experts of largest |E_i|, chosen once by the library's policy unit
@@ -374,6 +379,11 @@ def main():
                             score_host[l].copy_(rank_tensor(lay), non_blocking=True)
                             score_ev[l].record()
                             score_due[l] = True
+                        elif args.updates == "device":       # rule and loads on the GPU, nothing comes back
+                            before = lay.maps()[0] if not timed else None   # (untimed passes count the changes)
+                            lay.update_on_device(d1, d2, score=rank_tensor(lay))
+                            if not timed:
+                                swaps += int((lay.maps()[0] != before).sum())
                         else:
                             score = lay.policy_rank(lib_policy)      # the one host read-back per period
                             for sl, ex in lay.select_resident(score):
@@ -388,7 +398,9 @@ def main():
         swaps = run(warmup, steps, True)
         dt = time.perf_counter() - t0
         if use_events:          # the same steps again, instrumented (the resident set carries on from the first pass)
-            run(warmup, steps, False, instrument=True)
+            swaps2 = run(warmup, steps, False, instrument=True)
+            if args.updates == "device":
+                swaps = swaps2      # counted where reading the maps back costs nothing that is timed
         active_log = (offs_log[:, 1:] > offs_log[:, :-1]).sum(dim=1).cpu().numpy().tolist()
         hit_rate = None
         if args.hit_rate:
@@ -426,7 +438,7 @@ def main():
                     "hbm_frac": round(bytes_launch / avg / 1e9 / PEAK_HBM_GBS, 4)}
         else:
             act = float(np.mean(active_log)) if active_log else float(cfg.K)
-            default_c4 = (args.workload == "c4" and args.updates == "sync" and args.bank == "device"
+            default_c4 = (args.workload == "c4" and args.updates == "device" and args.bank == "device"
                           and args.policy == "importance" and args.period is None and not args.separate_calls
                           and args.decode_layers == 1)
             bytes_launch = 2.0 * act * cfg.d_model * cfg.d_ff  # one weight matrix of every active slot

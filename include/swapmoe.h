@@ -127,7 +127,8 @@ int smoe_set_resident(smoe_layer_t* layer, int slot, int expert, const void* w1_
                       const void* w2_src, void* stream);
 
 /* Host copies of the maps: slot_to_expert [K] (-1 = empty), expert_to_slot [E]
- * (-1 = not resident).  Either pointer may be NULL. */
+ * (-1 = not resident).  Either pointer may be NULL.  After smoe_update_on_device
+ * the call first waits for that update and fetches the device's maps. */
 int smoe_get_maps(const smoe_layer_t* layer, int32_t* slot_to_expert /*host*/,
                   int32_t* expert_to_slot /*host*/);
 
@@ -141,6 +142,21 @@ int smoe_get_maps(const smoe_layer_t* layer, int32_t* slot_to_expert /*host*/,
  * smoe_set_resident for each pair, in the order given. */
 int smoe_select_resident(const smoe_layer_t* layer, const float* score /*host*/,
                          int32_t* changed_slots /*host*/, int32_t* changed_experts /*host*/);
+
+/* The same update with nobody waiting for anybody (bf16 layers): the rule above
+ * is applied ON THE DEVICE to score [E] (device; what smoe_importance or
+ * smoe_forward leaves, or any other ranking), the device maps are switched, and
+ * the changed slots are loaded from the bank -- bank_w1 [E, d_model, d_ff],
+ * bank_w2 [E, d_ff, d_model], bf16 bit patterns in device or pinned host
+ * memory, indexed by expert id -- all enqueued on `stream` behind the work
+ * already there, with no read-back: the host learns the new maps only when it
+ * asks (smoe_get_maps and the other calls that consult the maps then wait for
+ * that stream once).  With the whole bank in GPU memory (288 GB hold every
+ * expert of the paper's models) this takes the controller's round trip out of
+ * the decode loop.  SMOE_ESTATE until every slot holds an expert, and while an
+ * asynchronous update (smoe_update_begin) is pending. */
+int smoe_update_on_device(smoe_layer_t* layer, const float* score /*device*/, const void* bank_w1,
+                          const void* bank_w2, void* stream);
 
 /* What ranks the experts at an update, for smoe_select_resident / smoe_update_begin:
  *   SMOE_POLICY_IMPORTANCE  the Eq. 1 score (SwapMoE's own scheduling)

@@ -66,6 +66,7 @@ _SIGS = {
     "smoe_profile_end": (C.c_int, [_vp, _vp, C.POINTER(C.c_float)]),
     "smoe_period_inflection": (C.c_int, [_vp, _i, C.c_float]),
     "smoe_describe_ffn": (C.c_int, [_vp, _i, _i, C.c_char_p, C.c_size_t]),
+    "smoe_update_on_device": (C.c_int, [_vp, _vp, _vp, _vp, _vp]),
     "smoe_profile_stream_read": (C.c_int, [_vp, _i, _vp]),
     "smoe_forward": (C.c_int, [_vp, _vp, _i, _vp, _vp, _i] + [_vp] * 12),
 }
@@ -249,6 +250,10 @@ def smoe_describe_ffn(layer, T, fused=True) -> str:
     return buf.value.decode()
 
 
+def smoe_update_on_device(layer, score_dev, bank_w1, bank_w2, stream=None):
+    _check(_lib.smoe_update_on_device(layer, _ptr(score_dev), _ptr(bank_w1), _ptr(bank_w2), _stream(stream)))
+
+
 def smoe_update_begin(layer, score_host) -> int:
     return _check(_lib.smoe_update_begin(layer, _ptr(score_host)))
 
@@ -326,6 +331,10 @@ class Layer:
 
     def set_resident(self, slot, expert, w1_src, w2_src):
         smoe_set_resident(self.handle, slot, expert, w1_src, w2_src)
+
+    def update_on_device(self, bank_w1, bank_w2, score=None):
+        """Update rule and slot loads on the device, from self.score unless another ranking is given."""
+        smoe_update_on_device(self.handle, self.score if score is None else score, bank_w1, bank_w2)
 
     def maps(self):
         import numpy as np

@@ -61,6 +61,7 @@ smoe_ws_layout smoe_ws_plan(const smoe_config& c) {
     w.e2s = off;     off = align_up(off + (size_t)c.E * 4, 256);
     w.s2e = off;     off = align_up(off + (size_t)c.K * 4, 256);
     w.phys = off;    off = align_up(off + (size_t)c.K * 4, 256);
+    w.dplan = off;   off = align_up(off + (size_t)(1 + 2 * c.K) * 4, 256);
     w.hist = off;    off = align_up(off + (size_t)smoe_sort_blocks(c.max_tokens) * c.K * 4, 256);
     w.hist32 = off;  off = align_up(off + (size_t)((c.max_tokens + 31) / 32) * c.K * 4, 256);
     // hidden activations: every segment is re-based to a multiple of 32 rows
@@ -85,6 +86,18 @@ static long long layer_slot_bytes(const smoe_config& c) {
 bool smoe_weights_outgrow_cache() {
     constexpr long long kCacheable = 192ll << 20;          // three quarters of the 256 MB Infinity Cache
     return g_live_slot_bytes.load(std::memory_order_relaxed) > kCacheable;
+}
+
+int smoe_refresh_maps(smoe_layer* L) {
+    if (!L->maps_stale) return SMOE_OK;
+    int rc = smoe_check_hip(hipStreamSynchronize(L->maps_stream), "maps: wait for the device-side update");
+    if (!rc) rc = smoe_check_hip(hipMemcpy(L->slot_to_expert.data(), L->d_slot_to_expert, (size_t)L->cfg.K * 4, hipMemcpyDeviceToHost),
+                                 "maps: read-back");
+    if (!rc) rc = smoe_check_hip(hipMemcpy(L->expert_to_slot.data(), L->d_expert_to_slot, (size_t)L->cfg.E * 4, hipMemcpyDeviceToHost),
+                                 "maps: read-back");
+    if (rc) return rc;
+    L->maps_stale = false;
+    return SMOE_OK;
 }
 
 extern "C" {
@@ -169,6 +182,8 @@ int smoe_bind(smoe_layer_t* L, const float* router_w, void* slot_w1, void* slot_
     L->d_expert_to_slot = (int32_t*)(L->workspace + w.e2s);
     L->d_slot_to_expert = (int32_t*)(L->workspace + w.s2e);
     L->d_phys = (int32_t*)(L->workspace + w.phys);
+    L->d_plan = (int32_t*)(L->workspace + w.dplan);
+    L->maps_stale = false;
     L->d_stage = L->workspace + w.stage;
     L->d_sort_hist = (int32_t*)(L->workspace + w.hist);
     L->d_hist32 = (int32_t*)(L->workspace + w.hist32);
@@ -199,6 +214,7 @@ int smoe_bind(smoe_layer_t* L, const float* router_w, void* slot_w1, void* slot_
 
 int smoe_get_maps(const smoe_layer_t* L, int32_t* slot_to_expert, int32_t* expert_to_slot) {
     if (!L) return smoe_fail(SMOE_EINVAL, "smoe_get_maps: null handle");
+    if (int rc = smoe_refresh_maps(const_cast<smoe_layer*>(L))) return rc;
     if (slot_to_expert) std::memcpy(slot_to_expert, L->slot_to_expert.data(), (size_t)L->cfg.K * 4);
     if (expert_to_slot) std::memcpy(expert_to_slot, L->expert_to_slot.data(), (size_t)L->cfg.E * 4);
     return SMOE_OK;
@@ -239,6 +255,7 @@ int smoe_set_resident(smoe_layer_t* L, int slot, int expert, const void* w1_src,
     if (!w1_src || !w2_src) return smoe_fail(SMOE_EINVAL, "smoe_set_resident: null weight source");
     if (misaligned(w1_src, 16) || misaligned(w2_src, 16))
         return smoe_fail(SMOE_EINVAL, "smoe_set_resident: weight sources must be 16-byte aligned");
+    if (int rc = smoe_refresh_maps(L)) return rc;
     int cur = L->expert_to_slot[expert];
     if (cur >= 0 && cur != slot)
         return smoe_fail(SMOE_ESTATE, "smoe_set_resident: expert %d is already resident in slot %d", expert, cur);
@@ -300,9 +317,42 @@ int smoe_select_resident(const smoe_layer_t* L, const float* score, int32_t* cha
     if (!L) return smoe_fail(SMOE_EINVAL, "smoe_select_resident: null handle");
     if (!score || !changed_slots || !changed_experts)
         return smoe_fail(SMOE_EINVAL, "smoe_select_resident: null argument");
+    if (int rc = smoe_refresh_maps(const_cast<smoe_layer*>(L))) return rc;
     int n = plan_changes(L->cfg, score, L->slot_to_expert, L->expert_to_slot, changed_slots, changed_experts);
     if (n < 0) return smoe_fail(SMOE_ESTATE, "smoe_select_resident: inconsistent maps");
     return n;
+}
+
+// ---- update without the host ------------------------------------------------
+
+int smoe_update_on_device(smoe_layer_t* L, const float* score, const void* bank_w1, const void* bank_w2, void* stream) {
+    if (!L) return smoe_fail(SMOE_EINVAL, "smoe_update_on_device: null handle");
+    if (!L->bound) return smoe_fail(SMOE_ESTATE, "smoe_update_on_device: call smoe_bind first");
+    if (L->cfg.dtype != SMOE_BF16) return smoe_fail(SMOE_EINVAL, "smoe_update_on_device: bf16 layers only");
+    if (!score || !bank_w1 || !bank_w2) return smoe_fail(SMOE_EINVAL, "smoe_update_on_device: null argument");
+    if (misaligned(score, 4) || misaligned(bank_w1, 16) || misaligned(bank_w2, 16))
+        return smoe_fail(SMOE_EINVAL, "smoe_update_on_device: score must be 4-byte, the banks 16-byte aligned");
+    if (L->slots_set != L->cfg.K) return smoe_fail(SMOE_ESTATE, "smoe_update_on_device: not every slot holds an expert");
+    if (!L->plan.empty() || !L->staged.empty())
+        return smoe_fail(SMOE_ESTATE, "smoe_update_on_device: an asynchronous update is pending");
+    // score and banks are read by kernels: checked once per triple of pointers
+    if (score != L->dev_update_seen[0] || bank_w1 != L->dev_update_seen[1] || bank_w2 != L->dev_update_seen[2]) {
+        int rc = check_gpu_readable(score, "smoe_update_on_device", "score");
+        if (!rc) rc = check_gpu_readable(bank_w1, "smoe_update_on_device", "bank_w1");
+        if (!rc) rc = check_gpu_readable(bank_w2, "smoe_update_on_device", "bank_w2");
+        if (rc) return rc;
+        L->dev_update_seen[0] = score; L->dev_update_seen[1] = bank_w1; L->dev_update_seen[2] = bank_w2;
+    }
+    hipStream_t s = as_stream(stream);
+    int rc = ensure_workspace(L, s);
+    if (rc) return rc;
+    // The host copies must be current before the device changes the maps again only if somebody
+    // reads them; they are marked stale and fetched on demand.
+    rc = smoe_launch_update_on_device(L, score, bank_w1, bank_w2, s);
+    if (rc) return rc;
+    L->maps_stale = true;
+    L->maps_stream = s;
+    return SMOE_OK;
 }
 
 // ---- asynchronous, amortized update ----------------------------------------
@@ -313,6 +363,7 @@ int smoe_update_begin(smoe_layer_t* L, const float* score) {
     if (L->cfg.spare_slots < 1) return smoe_fail(SMOE_ESTATE, "smoe_update_begin: the layer has no spare slot");
     if (!score) return smoe_fail(SMOE_EINVAL, "smoe_update_begin: null score");
     if (L->slots_set != L->cfg.K) return smoe_fail(SMOE_ESTATE, "smoe_update_begin: not every slot holds an expert");
+    if (int rc = smoe_refresh_maps(L)) return rc;
     // loads in flight count as done
     std::vector<int32_t> s2e = L->slot_to_expert, e2s = L->expert_to_slot;
     for (const auto& st : L->staged) {

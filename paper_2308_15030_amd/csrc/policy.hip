@@ -34,6 +34,7 @@ int smoe_on_demand_plan(smoe_layer_t* L, const int32_t* orig_expert, int T, int3
     const int E = L->cfg.E, K = L->cfg.K;
     if (T < 0 || (T > 0 && !orig_expert) || !changed_slots || !changed_experts)
         return smoe_fail(SMOE_EINVAL, "smoe_on_demand_plan: bad T or null argument");
+    if (int rc = smoe_refresh_maps(L)) return rc;
     // host maps only: an empty slot has never been used and is the first to be filled
     if ((int)L->last_use.size() != K) L->last_use.assign(K, 0);
     const int64_t now = ++L->use_clock;

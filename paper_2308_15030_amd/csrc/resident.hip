@@ -82,6 +82,87 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint16_t* __restri
     }
 }
 
+// The update rule (Section 3.2; important experts in, unimportant out) on the device, one
+// workgroup: the K highest scores form the new resident set (ties: lower expert id), experts that
+// stay keep their slots, the freed slots in ascending order receive the newcomers in descending
+// score.  Switches the device maps and leaves the loads in plan: [0] their number, [1 .. K] the
+// slots, [1 + K .. 2K] the experts.  E, K <= 256; every slot holds an expert (the host checks).
+__global__ __launch_bounds__(256) void plan_update_kernel(const float* __restrict__ score, int E, int K, int32_t* e2s,
+                                                          int32_t* s2e, int32_t* __restrict__ plan) {
+    __shared__ float s_score[256];
+    __shared__ int32_t s_e2s[256], s_s2e[256], s_rank[256], s_newc[256];
+    __shared__ unsigned char s_wanted[256], s_isnew[256], s_free[256];
+    const int tid = threadIdx.x;
+    s_score[tid] = tid < E ? score[tid] : 0.f;
+    s_e2s[tid] = tid < E ? e2s[tid] : 0;
+    s_s2e[tid] = tid < K ? s2e[tid] : -1;
+    s_newc[tid] = -1;
+    __syncthreads();
+    int rank = 0;                                          // experts that come before this one
+    if (tid < E) {
+        const float me = s_score[tid];
+        for (int j = 0; j < E; ++j) {
+            const float o = s_score[j];
+            rank += (o > me) | ((o == me) & (j < tid));
+        }
+    }
+    const bool wanted = tid < E && rank < K;
+    const bool isnew = wanted && s_e2s[tid] < 0;
+    s_rank[tid] = rank;
+    s_wanted[tid] = wanted;
+    s_isnew[tid] = isnew;
+    __syncthreads();
+    if (isnew) {                                           // newcomers in descending score
+        int ord = 0;
+        for (int j = 0; j < E; ++j) ord += s_isnew[j] && s_rank[j] < rank;
+        if (ord < 256) s_newc[ord] = tid;
+    }
+    bool fr = false;                                       // slots whose expert leaves
+    if (tid < K) {
+        const int cur = s_s2e[tid];
+        fr = !(cur >= 0 && s_wanted[cur]);
+    }
+    s_free[tid] = fr;
+    __syncthreads();
+    if (fr) {
+        int ord = 0;
+        for (int k = 0; k < tid; ++k) ord += s_free[k];
+        const int expert = ord < K ? s_newc[ord] : -1, old = s_s2e[tid];
+        if (expert >= 0) {                                 // (always, with consistent maps and finite scores)
+            plan[1 + ord] = tid;
+            plan[1 + K + ord] = expert;
+            if (old >= 0) e2s[old] = -1;
+            e2s[expert] = tid;
+            s2e[tid] = expert;
+        }
+    }
+    if (tid == 0) {                                        // pairs = the shorter of the two lists
+        int nf = 0, nn = 0;
+        for (int k = 0; k < K; ++k) nf += s_free[k];
+        for (int e = 0; e < E; ++e) nn += s_isnew[e];
+        plan[0] = nf < nn ? nf : nn;
+    }
+}
+
+// The planned loads from a bank [E][d_model][d_ff] / [E][d_ff][d_model] in GPU-readable memory:
+// workgroup b re-lays tile b of every planned expert in turn (the plan is short; most updates
+// change a few slots).
+__global__ __launch_bounds__(256) void pack_planned_kernel(const uint16_t* __restrict__ bank1, const uint16_t* __restrict__ bank2,
+                                                           int d_model, int d_ff, uint4* __restrict__ slot1,
+                                                           uint4* __restrict__ slot2, int nblk1, const int32_t* __restrict__ plan,
+                                                           int K, const int32_t* __restrict__ phys) {
+    __shared__ __align__(16) uint16_t lds[16 * PACK_LD];
+    const int n = plan[0];
+    const size_t per = (size_t)d_model * d_ff;             // elements per matrix
+    for (int j = 0; j < n; ++j) {
+        const int slot = plan[1 + j], expert = plan[1 + K + j];
+        const size_t dst = (size_t)phys[slot] * (per / 8);   // 16-byte units
+        if ((int)blockIdx.x < nblk1) pack_tile(bank1 + (size_t)expert * per, d_model, d_ff, slot1 + dst, blockIdx.x, lds);
+        else pack_tile(bank2 + (size_t)expert * per, d_ff, d_model, slot2 + dst, blockIdx.x - nblk1, lds);
+        __syncthreads();                                   // the tile buffer is reused by the next expert
+    }
+}
+
 __global__ __launch_bounds__(256) void copy16_kernel(const uint4* __restrict__ src, size_t n16,
                                                      uint4* __restrict__ dst) {
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -227,3 +308,15 @@ int smoe_launch_stream_read(const smoe_layer* L, int which, hipStream_t s) {
     return smoe_check_hip(hipGetLastError(), "smoe_profile_stream_read launch");
 }
 
+int smoe_launch_update_on_device(const smoe_layer* L, const float* score, const void* bank_w1, const void* bank_w2,
+                                 hipStream_t s) {
+    const smoe_config& c = L->cfg;
+    hipLaunchKernelGGL(plan_update_kernel, dim3(1), dim3(256), 0, s, score, c.E, c.K, L->d_expert_to_slot,
+                       L->d_slot_to_expert, L->d_plan);
+    const int nblk1 = (c.d_model / 16) * ((c.d_ff + PACK_COLS - 1) / PACK_COLS);
+    const int nblk2 = (c.d_ff / 16) * ((c.d_model + PACK_COLS - 1) / PACK_COLS);
+    hipLaunchKernelGGL(pack_planned_kernel, dim3(nblk1 + nblk2), dim3(256), 0, s, (const uint16_t*)bank_w1,
+                       (const uint16_t*)bank_w2, c.d_model, c.d_ff, (uint4*)L->slot_w1, (uint4*)L->slot_w2, nblk1,
+                       L->d_plan, c.K, L->d_phys);
+    return smoe_check_hip(hipGetLastError(), "smoe_update_on_device launch");
+}

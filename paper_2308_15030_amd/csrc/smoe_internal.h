@@ -49,12 +49,18 @@ struct smoe_layer {
     int32_t* d_expert_to_slot = nullptr;     // [E]
     int32_t* d_slot_to_expert = nullptr;     // [K]
     int32_t* d_phys = nullptr;               // [K] physical weight slot of each virtual slot
+    int32_t* d_plan = nullptr;               // [1 + 2K] smoe_update_on_device: number of loads, their slots, their experts
     int32_t* d_sort_hist = nullptr;          // [sort blocks, K]
     int32_t* d_hist32 = nullptr;             // fused path: [ceil(max_tokens/32), K] from the router
     void* d_hidden = nullptr;                // [max_tokens, d_ff] activations of the FFN
     float* d_partial = nullptr;              // small-T FFN: split partial sums
     float* d_norm_partial = nullptr;         // smoe_expert_norm: [E][64] partial sums of squares
     bool ws_ready = false;                   // device maps and counters initialised since the bind
+    // smoe_update_on_device changes the device maps without the host: the host copies are then
+    // stale until a call that needs them has fetched the device's (after waiting for that stream)
+    bool maps_stale = false;
+    hipStream_t maps_stream = nullptr;
+    const void* dev_update_seen[3] = {nullptr, nullptr, nullptr};   // pointers smoe_update_on_device has checked
     void* d_router_split = nullptr;          // bf16 path: router weights split in three, MFMA order
     bool router_split_done = false;          // made by the first smoe_route after a bind
 
@@ -68,7 +74,7 @@ struct smoe_layer {
 };
 
 struct smoe_ws_layout {
-    size_t e2s, s2e, phys, hist, hist32, hidden, partial, rsplit, norm, stage, total;
+    size_t e2s, s2e, phys, dplan, hist, hist32, hidden, partial, rsplit, norm, stage, total;
 };
 smoe_ws_layout smoe_ws_plan(const smoe_config& c);
 
@@ -136,6 +142,11 @@ int smoe_launch_set_map(const smoe_layer* L, int slot, int expert, int old_exper
 int smoe_launch_expert_norm(const smoe_layer* L, const void* w1, const void* w2, int n, float* out,
                             hipStream_t s);
 int smoe_launch_clear_maps(const smoe_layer* L, hipStream_t s);
+// update rule on the device from score [E] (device), then the planned loads from a device-readable bank
+int smoe_launch_update_on_device(const smoe_layer* L, const float* score, const void* bank_w1, const void* bank_w2,
+                                 hipStream_t s);
+// brings the host copies of the maps up to date after smoe_update_on_device (waits for its stream)
+int smoe_refresh_maps(smoe_layer* L);
 int smoe_launch_split_router(const smoe_layer* L, hipStream_t s);
 
 // Kernel launch that, when a pair of events is given, attaches them to the

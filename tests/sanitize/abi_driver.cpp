@@ -38,6 +38,7 @@ int smoe_launch_expert_norm(const smoe_layer*, const void*, const void*, int, fl
 int smoe_launch_clear_maps(const smoe_layer*, hipStream_t) { return 0; }
 int smoe_launch_split_router(const smoe_layer*, hipStream_t) { return 0; }
 int smoe_launch_stream_read(const smoe_layer*, int, hipStream_t) { return 0; }
+int smoe_launch_update_on_device(const smoe_layer*, const float*, const void*, const void*, hipStream_t) { return 0; }
 
 #define EXPECT(call, want) do { int rc_ = (call); if (rc_ != (want)) { printf("line %d: got %d, want %d (%s)\n", __LINE__, rc_, (int)(want), smoe_last_error()); return 1; } } while (0)
 
@@ -82,6 +83,7 @@ int main() {
     oe[0] = 99;
     EXPECT(smoe_on_demand_plan(h, oe.data(), (int)oe.size(), cs.data(), ce.data()), SMOE_EINVAL);
     EXPECT(smoe_update_begin(h, score.data()), SMOE_ESTATE);                   // slots are not filled
+    EXPECT(smoe_update_on_device(h, (float*)fake, fake, fake, nullptr), SMOE_ESTATE);   // slots are not filled
     EXPECT(smoe_update_tick(h, fake, fake, nullptr, nullptr), SMOE_EINVAL);    // banks are not GPU-readable memory
     EXPECT(smoe_update_pending(h), 0);
     // offline profile

@@ -87,6 +87,57 @@ def test_decode_with_updates(fused):
     L.close()
 
 
+def test_decode_with_updates_on_the_device():
+    """The same run with the update rule and the slot loads done by the device
+    (smoe_update_on_device): after every period the library's maps -- fetched
+    from the device on demand -- must equal the oracle's update rule applied to
+    the oracle's own scores (near ties at the K-th place aside), and every
+    step's outputs must match the oracle on the set the device has chosen."""
+    cfg = wl.CONFIGS["c4"]
+    c = Case(cfg, bank_experts=range(cfg.E), x=np.zeros((cfg.T, cfg.d_model), np.uint16))
+    L, T, K = c.L, cfg.T, cfg.K
+    steps = 96                                               # six updates
+    xs = wl.decode_stream(cfg, steps)
+    d_xs = to_dev(xs.reshape(steps * T, cfg.d_model)).view(steps, T, cfg.d_model)
+    s2e, e2s = c.s2e.copy(), c.e2s.copy()
+    state, swaps = None, 0
+    for step in range(steps):
+        first = step % cfg.period == 0
+        out = L.forward_fused(d_xs[step], T, accumulate=0 if first else 1)
+        torch.cuda.synchronize()
+        idx = [c.bank_pos[int(e)] for e in s2e]
+        ref = oracle.layer_forward(xs[step], c.Wr, c.W1_bank[idx], c.W2_bank[idx], e2s)
+        ok = ~ref["ambiguous"]
+        g_oe, g_slot = to_host(L.orig_expert), to_host(L.slot)
+        assert np.array_equal(g_oe[ok], ref["orig_expert"][ok]), step
+        assert np.array_equal(g_slot[ok], ref["slot"][ok]), step
+        state = oracle.importance(g_oe, ref["orig_gate"], ref["xnorm"], c.en_oracle, state=None if first else state)
+        assert np.array_equal(to_host(L.count), state[0]), step
+        np.testing.assert_allclose(to_host(L.score), state[2], rtol=1e-4, atol=1e-30)
+        err = max_abs_rel(values(to_host(out), cfg.dtype)[ok], values(ref["out"], cfg.dtype)[ok])
+        assert err <= 2e-2, (step, err)
+        if (step + 1) % cfg.period == 0:
+            L.update_on_device(c.d_W1, c.d_W2)               # ranks by L.score, on the device; no read-back here
+            n_s2e, n_e2s, ref_loads = oracle.select_resident(state[2], s2e, e2s)
+            g_s2e, g_e2s = L.maps()                          # waits for the update and fetches the device's maps
+            if not (np.array_equal(g_s2e, n_s2e) and np.array_equal(g_e2s, n_e2s)):
+                order = np.sort(state[2])[::-1]
+                gap = (order[K - 1] - order[K]) / max(order[K - 1], 1e-30)
+                assert gap < 1e-4, (step, g_s2e, n_s2e, gap)
+            # the maps are a consistent pair, whichever way a near tie went
+            assert sorted(g_s2e.tolist()) == sorted(np.nonzero(g_e2s >= 0)[0].tolist())
+            assert all(g_e2s[g_s2e[k]] == k for k in range(K))
+            swaps += int((g_s2e != s2e).sum())
+            s2e, e2s = g_s2e, g_e2s                          # the oracle follows the library's maps
+    assert swaps > 0, "the stream never changed the resident set: the test exercises nothing"
+    # pageable host memory is refused before any launch
+    from paper_2308_15030_amd import binding as b
+    with pytest.raises(b.SmoeError):
+        b.smoe_update_on_device(L.handle, L.score, np.zeros(4096, np.uint16), np.zeros(4096, np.uint16))
+    print(f"device-side updates: {swaps} experts swapped over {steps // cfg.period} updates", flush=True)
+    L.close()
+
+
 def test_decode_streaming_loads_same_bits():
     """Once the expert slots of the live layers outgrow the Infinity Cache the decode kernels
     read their weights with non-temporal loads (other kernel instances, same arithmetic): the
