@@ -136,12 +136,8 @@ __global__ __launch_bounds__(256) void plan_update_kernel(const float* __restric
             s2e[tid] = expert;
         }
     }
-    if (tid == 0) {                                        // pairs = the shorter of the two lists
-        int nf = 0, nn = 0;
-        for (int k = 0; k < K; ++k) nf += s_free[k];
-        for (int e = 0; e < E; ++e) nn += s_isnew[e];
-        plan[0] = nf < nn ? nf : nn;
-    }
+    const int nf = __syncthreads_count(fr), nn = __syncthreads_count(isnew);
+    if (tid == 0) plan[0] = nf < nn ? nf : nn;             // pairs = the shorter of the two lists
 }
 
 // The planned loads from a bank [E][d_model][d_ff] / [E][d_ff][d_model] in GPU-readable memory:
