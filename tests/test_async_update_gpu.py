@@ -180,6 +180,50 @@ def test_new_plan_while_a_load_is_in_flight():
     L.close()
 
 
+def test_device_side_update_after_slots_have_moved():
+    """smoe_update_on_device on a layer whose virtual slots no longer sit in their own physical
+    slots (asynchronous loads have been committed into the spare one): it must load into the
+    physical slot each virtual slot is mapped to, refuse to run while an asynchronous update is
+    pending, and leave maps that equal the oracle's rule.  Scores given by hand, small shape."""
+    cfg = wl.MoEConfig("device-update", E=8, K=3, d_model=64, d_ff=96, T=40, dtype=wl.BF16, seed=7)
+    c = Case(cfg, bank_experts=range(cfg.E), spare_slots=1)
+    L = c.L
+    ls = torch.cuda.Stream()
+    score1 = np.array([9, 8, 0, 0, 7, 0, 0, 0], np.float32)      # wants 0, 1, 4: expert 4 into slot 2 via the spare
+    assert L.update_begin(score1) == 1
+    d_score = torch.zeros(cfg.E, dtype=torch.float32, device=c.dev)
+    L.update_tick(c.d_W1, c.d_W2, ls)
+    with pytest.raises(b.SmoeError):                             # a load is in flight
+        b.smoe_update_on_device(L.handle, d_score, c.d_W1, c.d_W2)
+    for _ in range(12):
+        ls.synchronize()
+        L.update_tick(c.d_W1, c.d_W2, ls)
+        if L.update_pending() == 0:
+            break
+    assert L.update_pending() == 0 and L.maps()[0].tolist() == [0, 1, 4]
+    # now the device's turn, twice: a change of two slots, then nothing to change
+    score2 = np.array([0, 1, 0, 6, 5, 0, 0, 7], np.float32)      # wants 7, 3, 4: slots 0 and 1 go to 7 and 3
+    d_score.copy_(torch.from_numpy(score2))
+    s2e0, e2s0 = L.maps()
+    b.smoe_update_on_device(L.handle, d_score, c.d_W1, c.d_W2)
+    want_s2e, want_e2s, loads = oracle.select_resident(score2.astype(np.float64), s2e0, e2s0)
+    s2e, e2s = L.maps()
+    assert np.array_equal(s2e, want_s2e) and np.array_equal(e2s, want_e2s) and s2e.tolist() == [7, 3, 4]
+    out = L.forward_fused(c.d_x, c.T, accumulate=0)
+    ref = oracle.layer_forward(c.x, c.Wr, c.W1_bank[s2e], c.W2_bank[s2e], e2s)
+    torch.cuda.synchronize()
+    ok = ~ref["ambiguous"]
+    assert np.array_equal(to_host(L.slot)[ok], ref["slot"][ok])
+    assert max_abs_rel(values(to_host(out), cfg.dtype)[ok], values(ref["out"], cfg.dtype)[ok]) <= 2e-2
+    b.smoe_update_on_device(L.handle, d_score, c.d_W1, c.d_W2)  # same scores: nothing moves
+    assert L.maps()[0].tolist() == [7, 3, 4]
+    # the host-side calls see the device's maps: expert 7 is resident in slot 0 now
+    with pytest.raises(b.SmoeError):
+        L.set_resident(1, 7, c.d_W1[7], c.d_W2[7])
+    assert L.select_resident(score2) == []
+    L.close()
+
+
 def test_pageable_host_memory_is_refused_before_any_launch():
     """Weight sources and banks are read by kernels or by the copy engines: a numpy array
     (pageable host memory) must come back as SMOE_EINVAL from the host-side check, with no
