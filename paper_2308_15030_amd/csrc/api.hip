@@ -90,7 +90,13 @@ bool smoe_weights_outgrow_cache() {
 
 int smoe_refresh_maps(smoe_layer* L) {
     if (!L->maps_stale) return SMOE_OK;
-    int rc = smoe_check_hip(hipStreamSynchronize(L->maps_stream), "maps: wait for the device-side update");
+    // the stream the update ran on may be gone by now: then the whole device is waited for
+    hipError_t e = hipStreamSynchronize(L->maps_stream);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        e = hipDeviceSynchronize();
+    }
+    int rc = smoe_check_hip(e, "maps: wait for the device-side update");
     if (!rc) rc = smoe_check_hip(hipMemcpy(L->slot_to_expert.data(), L->d_slot_to_expert, (size_t)L->cfg.K * 4, hipMemcpyDeviceToHost),
                                  "maps: read-back");
     if (!rc) rc = smoe_check_hip(hipMemcpy(L->expert_to_slot.data(), L->d_expert_to_slot, (size_t)L->cfg.E * 4, hipMemcpyDeviceToHost),
