@@ -528,7 +528,7 @@ __global__ __launch_bounds__(NWR * 64) void route_mfma_kernel(
 // Decode step, first launch (bf16, at most 32 tokens, at most 64 experts): the router and the
 // first FFN product side by side.  The router of a 32-token batch is one workgroup that needs
 // ~9 us for 340 KB of operands, a softmax epilogue and the ranking tail, while the other 255
-// compute units wait for its slot ids only to learn which slots are empty.  Here the last
+// compute units wait for its slot ids only to learn which slots are empty.  Here the first
 // workgroup of the launch is that router, and the others compute the first product for EVERY
 // slot and EVERY token of the batch at once: workgroup (slot, feature tile) multiplies all T
 // tokens, staged once in LDS, by the slot's weight tile and stores the hidden activations
@@ -614,13 +614,14 @@ __device__ __forceinline__ void dense_first_all(const uint16_t* __restrict__ x, 
     int32_t* __restrict__ slot, float* __restrict__ gate, float* __restrict__ xnorm, int K, const TailArgs tail, \
     const uint4* __restrict__ W1, uint16_t* __restrict__ h, int d_ff, const int32_t* __restrict__ phys
 
+// Workgroup 0 is the router: it is the launch's critical path, so it is dispatched first.
 template <int NEB, bool STREAM>
 __device__ __forceinline__ void decode_first_body(SMOE_DECODE_FIRST_PARAMS) {
-    if (blockIdx.x == gridDim.x - 1)
+    if (blockIdx.x == 0)
         route_mfma_body<NEB, 8, 1>(0, x, Wsplit, e2s, T, d, E, gate_mode, orig_expert, orig_gate, slot, gate, xnorm,
                                    nullptr, K, tail);
     else
-        dense_first_all<STREAM>(x, W1, T, h, d, d_ff, phys, blockIdx.x);
+        dense_first_all<STREAM>(x, W1, T, h, d, d_ff, phys, blockIdx.x - 1);
 }
 
 // Two kernels with one body: the second streams its weights past the caches.
